@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the Gossip-PGA hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+gpga_local_grad (counter-RNG gradients written to the resident G buffer) followed
+by gpga_step (fused momentum + local update + gossip mix, or the exact all-node
+mean every H-th step).  All buffers (x, x_new, m, g) are resident in HBM before
+the timed region starts.
+
+Prints ONE JSON line.  `value` is steps/s of the whole path on the primary
+workload (cfg3: n=64, d=25.6M, the ResNet-50-sized configuration); the
+`roofline` object is for the dominant kernel (the fused gossip step), timed
+live with HIP events on the stream the kernels are launched on; `cpu_baseline`
+is the NumPy oracle timed on a bounded column slab of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
+
+# HBM bytes per launch of the fused gossip step measured with rocprofv3 --pmc
+# (FETCH_SIZE run + WRITE_SIZE run, scaled by a copy kernel of known size); the
+# summaries live under profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg3", help="primary workload: cfg3 or cfg4 (or cfg5 step-only)")
+    ap.add_argument("--topology", default=None, help="ring or expo1 (default: first listed for the workload)")
+    ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1",
+                    help="comma list of extra workload:topology pairs measured after the primary ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--opt", action="append", default=[], help="launch option name=value (repeatable)")
+    return ap.parse_args()
+
+
+def run_workload(cfg_name, topology, steps, warmup, opts):
+    """Times `steps` passes of local_grad + step.  Returns a dict of measurements."""
+    import torch
+
+    from paper_2105_09080_amd import inputs
+    from paper_2105_09080_amd.harness import Simulation
+
+    c = inputs.CONFIGS[cfg_name]
+    n, d = c["n"], c["d"]
+    stream = torch.cuda.Stream()
+    sim = Simulation(n, d, topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"], stream=stream)
+    for name, v in opts.items():
+        sim.set_option(name, v)
+    if c["problem"] == "synthetic":
+        sim.problem_synthetic(c["seed"], c["grad_var"])
+        grad = sim.local_grad
+    else:  # cfg5: virtual-feature logistic regression
+        y = inputs.virtual_labels(n, c["M"], c["seed"])
+        sim.problem_logreg_virtual(c["seed"], y, c["mu_var"])
+        idx = sim.upload_batches(inputs.batch_indices(steps + warmup, n, c["B"], c["M"], c["seed"]))
+        grad = lambda: sim.local_grad(idx[sim.k])
+
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            grad()
+            sim.step()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        kinds = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            k = sim.k
+            kinds.append("global" if (c["H"] > 0 and (k + 1) % c["H"] == 0) else "gossip")
+            ev[i][0].record()
+            grad()
+            ev[i][1].record()
+            sim.step()
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    grad_ms = [ev[i][0].elapsed_time(ev[i][1]) for i in range(steps)]
+    step_ms = [ev[i][1].elapsed_time(ev[i][2]) for i in range(steps)]
+    gossip = [t for t, kd in zip(step_ms, kinds) if kd == "gossip"]
+    glob = [t for t, kd in zip(step_ms, kinds) if kd == "global"]
+    elts = n * d
+    res = {
+        "workload": f"{cfg_name}: n={n} d={d} {topology} H={c['H']} momentum={c['momentum']}",
+        "n": n, "d": d, "topology": topology, "H": c["H"],
+        "wall_s": t1 - t0,
+        "ms_per_step": 1e3 * (t1 - t0) / steps,
+        "steps_per_s": steps / (t1 - t0),
+        "grad_ms_avg": sum(grad_ms) / steps,
+        "step_ms_avg": sum(step_ms) / steps,
+        "gossip_ms_avg": sum(gossip) / len(gossip) if gossip else None,
+        "global_ms_avg": sum(glob) / len(glob) if glob else None,
+        "n_gossip": len(gossip), "n_global": len(glob),
+        "algorithmic_bytes_per_launch": BYTES_PER_ELT * elts,
+    }
+    dom = res["gossip_ms_avg"] if gossip else res["global_ms_avg"]
+    res["dominant"] = "gossip" if gossip else "global"
+    res["achieved_gbs"] = BYTES_PER_ELT * elts / (dom * 1e-3) / 1e9
+    if glob:
+        res["global_gbs"] = BYTES_PER_ELT * elts / (res["global_ms_avg"] * 1e-3) / 1e9
+    res["grad_write_gbs"] = 4 * elts / (res["grad_ms_avg"] * 1e-3) / 1e9
+    res["step_only_steps_per_s"] = 1e3 / res["step_ms_avg"]
+    res["consensus_error_final"] = sim.consensus_error()
+    sim.close()
+    del sim
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(cfg_name, topology, budget_s=15.0):
+    """The oracle as it stands on a column slab of the workload (the recursion is
+    column-separable with synthetic gradients), scaled to the full width."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import gpga_oracle as orc
+    from paper_2105_09080_amd import inputs
+
+    c = inputs.CONFIGS[cfg_name]
+    n, d = c["n"], c["d"]
+    slab = 65536
+    cols = np.arange(slab)
+    ref = orc.GossipPGA(n, slab, topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"], storage="f32")
+    t0 = time.perf_counter()
+    steps = 0
+    while True:
+        G = orc.synthetic_grad(c["seed"], steps, n, cols, c["grad_var"])
+        ref.step(G)
+        steps += 1
+        if time.perf_counter() - t0 > budget_s or steps >= c["T"]:
+            break
+    dt = (time.perf_counter() - t0) / steps
+    full_step_s = dt * d / slab
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {
+        "value": 1.0 / full_step_s, "unit": "steps/s", "cores": threads, "kind": "oracle",
+        "sample": f"{steps} steps of the NumPy float64 oracle (gradient generation + step) on a {n}x{slab} "
+                  f"column slab of {cfg_name}/{topology}; {dt:.3f} s per slab step, scaled by d/slab = {d / slab:.1f} "
+                  f"(columns are independent); BLAS threads {threads} of {os.cpu_count()} host CPUs, "
+                  f"the counter-RNG part is single-threaded NumPy",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (n simulated nodes on one MI355X); "
+              "--gpus must be 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2105_09080_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    opts = {}
+    for o in args.opt:
+        name, v = o.split("=")
+        opts[name] = int(v)
+
+    topo = args.topology or inputs.CONFIGS[args.config]["topologies"][0]
+    main_res = run_workload(args.config, topo, args.steps, args.warmup, opts)
+    others = []
+    for item in [s for s in args.also.split(",") if s]:
+        name, tp = item.split(":")
+        if (name, tp) == (args.config, topo):
+            continue
+        steps = min(args.steps, inputs.CONFIGS[name]["T"])
+        others.append(run_workload(name, tp, steps, args.warmup, opts))
+
+    out = {
+        "metric": "Gossip-PGA steps/s and achieved HBM GB/s (% of peak) for fused n x d step",
+        "value": main_res["steps_per_s"],
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": main_res["workload"], "options": opts,
+                   "step": "gpga_local_grad (counter-RNG gradients) + gpga_step (fused update + mix/average)"},
+        "node_updates_per_s": main_res["steps_per_s"] * main_res["n"],
+        "step_only_steps_per_s": main_res["step_only_steps_per_s"],
+        "roofline": {
+            "bound": "hbm",
+            "kernel": f"fused {main_res['dominant']} step (k_step_walk)" if main_res["dominant"] == "gossip"
+                      else "fused global-average step (k_step_global)",
+            "achieved": main_res["achieved_gbs"],
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": main_res["achieved_gbs"] / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(f"{args.config}/{topo}"),
+            "algorithmic_bytes_per_launch": main_res["algorithmic_bytes_per_launch"],
+            "avg_launch_ms": main_res["gossip_ms_avg"] if main_res["dominant"] == "gossip" else main_res["global_ms_avg"],
+            "global_step_avg_ms": main_res["global_ms_avg"],
+            "global_step_gbs": main_res.get("global_gbs"),
+        },
+        "breakdown": {"grad_ms_avg": main_res["grad_ms_avg"], "step_ms_avg": main_res["step_ms_avg"],
+                      "grad_write_gbs": main_res["grad_write_gbs"],
+                      "n_gossip": main_res["n_gossip"], "n_global": main_res["n_global"]},
+        "other_workloads": [
+            {"workload": r["workload"], "steps_per_s": r["steps_per_s"], "step_only_steps_per_s": r["step_only_steps_per_s"],
+             "ms_per_step": r["ms_per_step"], "gossip_ms_avg": r["gossip_ms_avg"], "global_ms_avg": r["global_ms_avg"],
+             "grad_ms_avg": r["grad_ms_avg"], "achieved_gbs": r["achieved_gbs"], "frac": r["achieved_gbs"] / HBM_PEAK_GBS,
+             "global_step_gbs": r.get("global_gbs")} for r in others],
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, topo)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,166 @@
+/*
+ * gpga.h - C ABI of libgpga: the Gossip-PGA iteration for n simulated nodes on
+ * one MI355X (gfx950).
+ *
+ * The method is Gossip SGD with Periodic Global Averaging (arXiv 2105.09080).
+ * Problem statement (Sec. 1, eq. (1)): n nodes minimise (1/n) sum_i f_i(x),
+ * x in R^d; node i can only evaluate stochastic gradients of its own f_i.
+ * Algorithm 1 (Sec. 3), for k = 0..T-1 and every node i:
+ *     g_i      = grad F_i(x_i^(k); xi_i)                  (gpga_local_grad)
+ *     x_i^(k+1/2) = x_i^(k) - gamma * g_i                 \
+ *     if mod(k+1, H) == 0:  x_i^(k+1) = (1/n) sum_j x_j^(k+1/2)     } gpga_step
+ *     else:                 x_i^(k+1) = sum_{j in N_i} w_ij x_j^(k+1/2) /
+ * with W doubly stochastic, all x_i^(0) equal.  In matrix form (App. A):
+ * X <- W (X - gamma G) or X <- (1/n) 1 1^T (X - gamma G), X in R^{n x d}.
+ *
+ * Data layout: every state array is node-major fp32, row i = node i, with a
+ * common leading dimension ld >= d (in floats).  All pointers named *_dev are
+ * DEVICE pointers owned by the caller (the library never allocates or frees
+ * n x d memory; it owns only the context and small scratch for reductions and
+ * per-sample coefficients).  Work is enqueued on the stream given to
+ * gpga_bind and is asynchronous unless stated otherwise.
+ *
+ * Errors: every call returns a gpga_status; nothing aborts or throws across
+ * the ABI.  gpga_last_error(ctx) returns a static-lifetime-of-ctx string that
+ * describes the most recent failure on that context.  Invalid arguments are
+ * rejected before anything is launched.  A context is not thread-safe.
+ */
+#ifndef GPGA_H
+#define GPGA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gpga_ctx gpga_ctx; /* opaque */
+
+typedef enum {
+    GPGA_OK = 0,
+    GPGA_EINVAL = 1,  /* bad argument (size, range, alignment, NULL)           */
+    GPGA_ENOMEM = 2,  /* host or device scratch allocation failed              */
+    GPGA_EDEVICE = 3, /* a HIP call or kernel launch reported an error         */
+    GPGA_ESTATE = 4   /* call order: buffers not bound / no problem attached   */
+} gpga_status;
+
+/* Mixing graphs.  Sec. 3: W = I turns the method into Local SGD, W = (1/n)11^T
+ * into parallel SGD; H -> infinity (H = 0 here) into plain Gossip SGD. */
+typedef enum {
+    GPGA_TOPO_RING = 0,  /* self + two ring neighbours, weights 1/3 (|N_i| = 3, Sec. 3.3;
+                            reproduces the beta values printed in Sec. 5.1)              */
+    GPGA_TOPO_EXPO1 = 1, /* time-varying one-peer exponential graph (App. F.1): at
+                            iteration k row i averages with row (i + 2^(k mod tau)) mod n,
+                            tau = ceil(log2 n), weights 1/2                             */
+    GPGA_TOPO_NONE = 2,  /* W = I                                                        */
+    GPGA_TOPO_FULL = 3   /* W = (1/n) 1 1^T : every step is a global average             */
+} gpga_topology;
+
+/* Algorithm 1 "Require": learning rate gamma = lr > 0 (finite), weight matrix
+ * (topology), averaging period H (H >= 1; H = 0 means never average).  momentum
+ * in [0,1) selects heavy-ball SGD as used in the paper's experiments (App. F.1):
+ * m <- momentum*m + g, x^(k+1/2) = x - lr*m; momentum = 0 is Algorithm 1 exactly.
+ * n >= 1 nodes, d >= 1 parameters.  Binds the context to the current HIP device.
+ * On success *out receives a context to be released with gpga_destroy. */
+gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology,
+                        int64_t H, float lr, float momentum);
+
+/* Waits for the bound stream, frees library scratch and the context. */
+gpga_status gpga_destroy(gpga_ctx* ctx);
+
+/* Attach caller-owned device buffers, each n rows x ld floats (ld >= d):
+ *   x_dev     current iterates X^(k)         (read by local_grad/step)
+ *   x_new_dev receives X^(k+1)               (must not alias x_dev)
+ *   m_dev     momentum buffer, updated in place (may be NULL iff momentum == 0)
+ *   g_dev     stochastic gradients G^(k): written by gpga_local_grad, or by the
+ *             caller itself (e.g. a real backward pass) before gpga_step
+ * After each gpga_step the roles of x_dev and x_new_dev swap (gpga_current_x).
+ * Pointers must be 4-byte aligned; 16-byte aligned pointers with ld % 4 == 0
+ * take the 128-bit path.  hip_stream is a hipStream_t (NULL = default stream). */
+gpga_status gpga_bind(gpga_ctx* ctx, float* x_dev, float* x_new_dev, float* m_dev,
+                      float* g_dev, int64_t ld, void* hip_stream);
+
+/* Algorithm 1 "Require": all x_i^(0) identical.  Sets every row of the live X to
+ * x0_dev (d floats on the device; NULL = zeros), m to zero and k to 0. */
+gpga_status gpga_reset(gpga_ctx* ctx, const float* x0_dev);
+
+gpga_status gpga_set_lr(gpga_ctx* ctx, float lr);
+gpga_status gpga_set_period(gpga_ctx* ctx, int64_t H);
+/* Set the iteration counter k (resume): k drives the averaging schedule, the
+ * one-peer offset and the address of synthetic gradients. */
+gpga_status gpga_set_iter(gpga_ctx* ctx, int64_t k);
+int64_t gpga_iter(const gpga_ctx* ctx);
+
+/* ---- local objectives f_i (the "stochastic gradient" slot of Algorithm 1) ----
+ * Data arrays are device pointers, borrowed until another problem is attached. */
+
+/* Least squares: f_i(x) = 1/(2|B|) ||A_i[B] x - b_i[B]||^2.
+ * A_dev: n x M x d fp32 (row-major, dense), b_dev: n x M fp32. */
+gpga_status gpga_problem_lsq(gpga_ctx* ctx, const float* A_dev, const float* b_dev, int32_t M);
+
+/* Logistic regression (Sec. 5.1): f_i(x) = (1/|B|) sum_{m in B} ln(1 + exp(-y_m h_m^T x)).
+ * feat_dev: n x M x d fp32, y_dev: n x M fp32 holding +1 / -1. */
+gpga_status gpga_problem_logreg(gpga_ctx* ctx, const float* feat_dev, const float* y_dev,
+                                int32_t M);
+
+/* Logistic regression whose features are never stored: h_{i,m}[c] = mu_i[c] + zeta,
+ * mu_i[c] = sqrt(mu_var) * N(seed, 3, i, 0, c), zeta = N(seed, 2, i, m, c), where
+ * N(seed, tag, a, b, c) is the counter-addressed standard normal defined below.
+ * y_dev: n x M fp32 labels (+1 / -1). */
+gpga_status gpga_problem_logreg_virtual(gpga_ctx* ctx, uint64_t seed, const float* y_dev,
+                                        int32_t M, float mu_var);
+
+/* Synthetic gradients standing in for a network's backward pass:
+ * G[i][c] = sqrt(grad_var) * N(seed, 1, i, k, c), k = current iteration.
+ *
+ * N(seed, tag, a, b, c): Philox4x32-10 (Salmon et al., SC'11) with key
+ * (seed & 0xffffffff, seed >> 32) and counter (c / 4, a, b, tag) gives words
+ * r0..r3; u_j = ((r_j >> 9) + 0.5) * 2^-23; Box-Muller:
+ * (sqrt(-2 ln u0) cos 2 pi u1, sqrt(-2 ln u0) sin 2 pi u1) are columns 4*(c/4)+0,1
+ * and the same with (u2, u3) columns +2,+3. */
+gpga_status gpga_problem_synthetic(gpga_ctx* ctx, uint64_t seed, float grad_var);
+
+/* g_i = grad F_i(x_i^(k); xi_i) for every node i at its own current row x_i,
+ * written to g_dev.  batch_idx_dev: n x B int32 sample indices in [0, M) (the
+ * minibatch xi_i, drawn by the caller); NULL with B = 0 means the full local
+ * dataset.  Ignored for the synthetic problem.  ESTATE without bind/problem. */
+gpga_status gpga_local_grad(gpga_ctx* ctx, const int32_t* batch_idx_dev, int32_t B);
+
+/* Loss companion of gpga_local_grad (used by adaptive averaging, Alg. 2):
+ * loss_dev[i] = F_i(x_i^(k); xi_i) for the same minibatch, n floats on the
+ * device.  Not available for the synthetic problem (EINVAL). */
+gpga_status gpga_local_loss(gpga_ctx* ctx, const int32_t* batch_idx_dev, int32_t B,
+                            float* loss_dev);
+
+/* One iteration of Algorithm 1 lines 2-6 as a single fused kernel: momentum and
+ * local update, then the global average if mod(k+1, H) == 0 (H > 0) or
+ * topology == FULL, else one gossip step with W_k.  Reads x, m, g once, writes
+ * m and x_new once; then swaps x / x_new and increments k. */
+gpga_status gpga_step(gpga_ctx* ctx);
+
+/* Consensus distance ||X^(k) - 1 xbar^T||_F (Sec. 4; App. B) of the live X.
+ * Synchronises the stream; *out_host is a host double. */
+gpga_status gpga_consensus_error(gpga_ctx* ctx, double* out_host);
+
+/* xbar = (1/n) sum_i x_i (App. A notation) of the live X into xbar_dev (d floats
+ * on the device, caller-owned). */
+gpga_status gpga_mean(gpga_ctx* ctx, float* xbar_dev);
+
+/* Device pointer of the live X (x_dev or x_new_dev of gpga_bind). */
+gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
+
+/* Launch-geometry overrides for measurement sweeps; values outside the
+ * documented range give EINVAL.  Names: "unroll" (rows in flight per lane: 1, 2,
+ * 4, 8), "waves" (wavefronts per workgroup: 1, 2, 4, 8), "row_split" (wavefronts
+ * sharing one column tile along the node axis, 0 = automatic, else 1, 2, 4, 8;
+ * must not exceed "waves"), "row_lanes" (global-average kernel: lanes of a
+ * wavefront spread over rows: 0 = automatic, 1, 2, 4), "xcd_swizzle" (0/1). */
+gpga_status gpga_set_option(gpga_ctx* ctx, const char* name, int64_t value);
+
+const char* gpga_last_error(const gpga_ctx* ctx);
+const char* gpga_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPGA_H */

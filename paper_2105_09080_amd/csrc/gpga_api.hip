@@ -1,0 +1,415 @@
+// C ABI of libgpga (see include/gpga.h): argument validation, the averaging
+// schedule of Algorithm 1 (global average iff mod(k+1, H) == 0), the one-peer
+// offset schedule, scratch management and kernel dispatch.  All heavy work is
+// in the kernels; the host code here decides *which* fused kernel runs.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "gpga_internal.hpp"
+
+namespace {
+
+void set_err(gpga_ctx* c, const char* fmt, ...) {
+    if (!c) return;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+}
+
+gpga_status fail(gpga_ctx* c, gpga_status s, const char* fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+gpga_status hip_fail(gpga_ctx* c, hipError_t e, const char* what) {
+    if (e == hipErrorOutOfMemory) return fail(c, GPGA_ENOMEM, "%s: %s", what, hipGetErrorString(e));
+    return fail(c, GPGA_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Makes the context's device current for the duration of a call.
+struct DeviceGuard {
+    int prev = -1;
+    bool changed = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) changed = (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard() {
+        if (changed) (void)hipSetDevice(prev);
+    }
+};
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int tau_of(int32_t n) {  // number of offsets of the one-peer exponential graph
+    int t = 0;
+    while ((1LL << t) < n) ++t;
+    return t < 1 ? 1 : t;
+}
+
+bool is_pow2_le8(int64_t v) { return v == 1 || v == 2 || v == 4 || v == 8; }
+
+gpga_status grow_f32(gpga_ctx* c, float** p, size_t* cap, size_t need) {
+    if (*cap >= need) return GPGA_OK;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    if (*p) (void)hipFree(*p);
+    *p = nullptr;
+    *cap = 0;
+    e = hipMalloc(reinterpret_cast<void**>(p), need * sizeof(float));
+    if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(scratch)");
+    *cap = need;
+    return GPGA_OK;
+}
+
+gpga_status grow_f64(gpga_ctx* c, double** p, size_t* cap, size_t need) {
+    if (*cap >= need) return GPGA_OK;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    if (*p) (void)hipFree(*p);
+    *p = nullptr;
+    *cap = 0;
+    e = hipMalloc(reinterpret_cast<void**>(p), need * sizeof(double));
+    if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(scratch)");
+    *cap = need;
+    return GPGA_OK;
+}
+
+gpga_status check_batch(gpga_ctx* c, const int32_t* idx, int32_t B, int32_t* Beff) {
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    if (c->problem == PROB_NONE) return fail(c, GPGA_ESTATE, "no problem attached (gpga_problem_*)");
+    if (c->problem == PROB_SYNTH) {
+        *Beff = 0;
+        return GPGA_OK;
+    }
+    if (idx == nullptr) {
+        if (B != 0) return fail(c, GPGA_EINVAL, "batch_idx_dev is NULL but B = %d (full batch needs B = 0)", B);
+        if (c->problem == PROB_LOGREG_VIRTUAL)
+            return fail(c, GPGA_EINVAL, "the virtual-feature problem needs an explicit minibatch");
+        *Beff = c->M;
+    } else {
+        if (B < 1) return fail(c, GPGA_EINVAL, "B = %d must be >= 1 with a minibatch table", B);
+        if (!aligned(idx, 4)) return fail(c, GPGA_EINVAL, "batch_idx_dev is not 4-byte aligned");
+        if (c->problem == PROB_LOGREG_VIRTUAL && B > 32)
+            return fail(c, GPGA_EINVAL, "virtual-feature problem supports B <= 32 (got %d)", B);
+        *Beff = B;
+    }
+    if ((int64_t)*Beff > 65535 * 1024LL) return fail(c, GPGA_EINVAL, "batch too large");
+    return GPGA_OK;
+}
+
+gpga_status run_grad(gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out) {
+    int32_t Beff = 0;
+    gpga_status s = check_batch(c, idx, B, &Beff);
+    if (s != GPGA_OK) return s;
+    DeviceGuard guard(c->device);
+    hipError_t e = hipSuccess;
+    if (c->problem == PROB_SYNTH) {
+        if (loss_out) return fail(c, GPGA_EINVAL, "the synthetic problem has no loss");
+        e = launch_synth_grad(c);
+    } else {
+        s = grow_f32(c, &c->coef, &c->coef_cap, (size_t)2 * c->n * Beff);
+        if (s != GPGA_OK) return s;
+        if (c->problem == PROB_LOGREG_VIRTUAL) {
+            size_t need = (size_t)c->n * Beff;
+            const size_t cons = consensus_partials_needed(c);
+            if (need < cons) need = cons;
+            s = grow_f64(c, &c->partials, &c->partials_cap, need);
+            if (s != GPGA_OK) return s;
+            e = launch_virtual_grad(c, idx, Beff, loss_out);
+        } else {
+            e = launch_rows_grad(c, idx, idx ? Beff : 0, loss_out);
+        }
+    }
+    if (e != hipSuccess) return hip_fail(c, e, "gradient kernel launch");
+    return GPGA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gpga_version(void) { return "libgpga 0.1 (gfx950)"; }
+
+gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, int64_t H, float lr,
+                        float momentum) {
+    if (!out) return GPGA_EINVAL;
+    *out = nullptr;
+    if (n < 1 || n > (1 << 24)) return GPGA_EINVAL;
+    if (d < 1 || d > (int64_t)0xffffffffLL * 4) return GPGA_EINVAL;  // column quad index is 32-bit
+    if (topology < GPGA_TOPO_RING || topology > GPGA_TOPO_FULL) return GPGA_EINVAL;
+    if (H < 0) return GPGA_EINVAL;
+    if (!std::isfinite(lr) || lr < 0.f) return GPGA_EINVAL;
+    if (!(momentum >= 0.f && momentum < 1.f)) return GPGA_EINVAL;
+    gpga_ctx* c = new (std::nothrow) gpga_ctx();
+    if (!c) return GPGA_ENOMEM;
+    c->n = n;
+    c->d = d;
+    c->topo = topology;
+    c->H = H;
+    c->lr = lr;
+    c->mu = momentum;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        delete c;
+        return GPGA_EDEVICE;
+    }
+    const size_t need = consensus_partials_needed(c);
+    if (hipMalloc(reinterpret_cast<void**>(&c->partials), need * sizeof(double)) != hipSuccess) {
+        delete c;
+        return GPGA_ENOMEM;
+    }
+    c->partials_cap = need;
+    if (hipHostMalloc(reinterpret_cast<void**>(&c->host_scalar), sizeof(double), hipHostMallocDefault) !=
+        hipSuccess) {
+        (void)hipFree(c->partials);
+        delete c;
+        return GPGA_ENOMEM;
+    }
+    *out = c;
+    return GPGA_OK;
+}
+
+gpga_status gpga_destroy(gpga_ctx* c) {
+    if (!c) return GPGA_EINVAL;
+    DeviceGuard guard(c->device);
+    gpga_status s = GPGA_OK;
+    if (c->bound && hipStreamSynchronize(c->stream) != hipSuccess) s = GPGA_EDEVICE;
+    if (c->coef) (void)hipFree(c->coef);
+    if (c->partials) (void)hipFree(c->partials);
+    if (c->host_scalar) (void)hipHostFree(c->host_scalar);
+    delete c;
+    return s;
+}
+
+gpga_status gpga_bind(gpga_ctx* c, float* x, float* x_new, float* m, float* g, int64_t ld,
+                      void* hip_stream) {
+    if (!c) return GPGA_EINVAL;
+    if (!x || !x_new || !g) return fail(c, GPGA_EINVAL, "x, x_new and g must not be NULL");
+    if (!m && c->mu != 0.f) return fail(c, GPGA_EINVAL, "m may be NULL only when momentum == 0");
+    if (x == x_new) return fail(c, GPGA_EINVAL, "x_new must not alias x");
+    if (ld < c->d) return fail(c, GPGA_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)c->d);
+    if (!aligned(x, 4) || !aligned(x_new, 4) || !aligned(g, 4) || (m && !aligned(m, 4)))
+        return fail(c, GPGA_EINVAL, "buffers must be 4-byte aligned");
+    c->x = x;
+    c->x_new = x_new;
+    c->m = m;
+    c->g = g;
+    c->ld = ld;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->bound = true;
+    return GPGA_OK;
+}
+
+gpga_status gpga_reset(gpga_ctx* c, const float* x0_dev) {
+    if (!c) return GPGA_EINVAL;
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    if (x0_dev && !aligned(x0_dev, 4)) return fail(c, GPGA_EINVAL, "x0 must be 4-byte aligned");
+    DeviceGuard guard(c->device);
+    hipError_t e = launch_fill_rows(c, c->x, x0_dev);
+    if (e == hipSuccess && c->m) e = launch_fill_rows(c, c->m, nullptr);
+    if (e != hipSuccess) return hip_fail(c, e, "fill kernel launch");
+    c->k = 0;
+    return GPGA_OK;
+}
+
+gpga_status gpga_set_lr(gpga_ctx* c, float lr) {
+    if (!c) return GPGA_EINVAL;
+    if (!std::isfinite(lr) || lr < 0.f) return fail(c, GPGA_EINVAL, "lr must be finite and >= 0");
+    c->lr = lr;
+    return GPGA_OK;
+}
+
+gpga_status gpga_set_period(gpga_ctx* c, int64_t H) {
+    if (!c) return GPGA_EINVAL;
+    if (H < 0) return fail(c, GPGA_EINVAL, "H must be >= 0 (0 = never average)");
+    c->H = H;
+    return GPGA_OK;
+}
+
+gpga_status gpga_set_iter(gpga_ctx* c, int64_t k) {
+    if (!c) return GPGA_EINVAL;
+    if (k < 0) return fail(c, GPGA_EINVAL, "k must be >= 0");
+    c->k = k;
+    return GPGA_OK;
+}
+
+int64_t gpga_iter(const gpga_ctx* c) { return c ? c->k : -1; }
+
+gpga_status gpga_problem_lsq(gpga_ctx* c, const float* A, const float* b, int32_t M) {
+    if (!c) return GPGA_EINVAL;
+    if (!A || !b || M < 1) return fail(c, GPGA_EINVAL, "A, b must not be NULL and M >= 1");
+    if (!aligned(A, 4) || !aligned(b, 4)) return fail(c, GPGA_EINVAL, "A, b must be 4-byte aligned");
+    c->problem = PROB_LSQ;
+    c->feat = A;
+    c->tgt = b;
+    c->M = M;
+    return GPGA_OK;
+}
+
+gpga_status gpga_problem_logreg(gpga_ctx* c, const float* feat, const float* y, int32_t M) {
+    if (!c) return GPGA_EINVAL;
+    if (!feat || !y || M < 1) return fail(c, GPGA_EINVAL, "feat, y must not be NULL and M >= 1");
+    if (!aligned(feat, 4) || !aligned(y, 4)) return fail(c, GPGA_EINVAL, "feat, y must be 4-byte aligned");
+    c->problem = PROB_LOGREG;
+    c->feat = feat;
+    c->tgt = y;
+    c->M = M;
+    return GPGA_OK;
+}
+
+gpga_status gpga_problem_logreg_virtual(gpga_ctx* c, uint64_t seed, const float* y, int32_t M,
+                                        float mu_var) {
+    if (!c) return GPGA_EINVAL;
+    if (!y || M < 1) return fail(c, GPGA_EINVAL, "y must not be NULL and M >= 1");
+    if (!aligned(y, 4)) return fail(c, GPGA_EINVAL, "y must be 4-byte aligned");
+    if (!std::isfinite(mu_var) || mu_var < 0.f) return fail(c, GPGA_EINVAL, "mu_var must be finite and >= 0");
+    c->problem = PROB_LOGREG_VIRTUAL;
+    c->feat = nullptr;
+    c->tgt = y;
+    c->M = M;
+    c->seed = seed;
+    c->mu_sigma = std::sqrt(mu_var);
+    return GPGA_OK;
+}
+
+gpga_status gpga_problem_synthetic(gpga_ctx* c, uint64_t seed, float grad_var) {
+    if (!c) return GPGA_EINVAL;
+    if (!std::isfinite(grad_var) || grad_var < 0.f) return fail(c, GPGA_EINVAL, "grad_var must be finite and >= 0");
+    c->problem = PROB_SYNTH;
+    c->feat = nullptr;
+    c->tgt = nullptr;
+    c->M = 0;
+    c->seed = seed;
+    c->grad_sigma = std::sqrt(grad_var);
+    return GPGA_OK;
+}
+
+gpga_status gpga_local_grad(gpga_ctx* c, const int32_t* batch_idx, int32_t B) {
+    if (!c) return GPGA_EINVAL;
+    return run_grad(c, batch_idx, B, nullptr);
+}
+
+gpga_status gpga_local_loss(gpga_ctx* c, const int32_t* batch_idx, int32_t B, float* loss_dev) {
+    if (!c) return GPGA_EINVAL;
+    if (!loss_dev || !aligned(loss_dev, 4)) return fail(c, GPGA_EINVAL, "loss_dev must be a 4-byte aligned device pointer");
+    return run_grad(c, batch_idx, B, loss_dev);
+}
+
+gpga_status gpga_step(gpga_ctx* c) {
+    if (!c) return GPGA_EINVAL;
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    DeviceGuard guard(c->device);
+
+    const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
+    int mode = MODE_SELF;
+    int32_t S = 0;
+    if (!global && c->n > 1) {
+        if (c->topo == GPGA_TOPO_RING) {
+            mode = MODE_RING;
+            S = 1;
+        } else if (c->topo == GPGA_TOPO_EXPO1) {
+            S = (int32_t)((1LL << (c->k % tau_of(c->n))) % c->n);
+            mode = S ? MODE_PEER : MODE_SELF;
+        }
+    }
+
+    const bool vec = aligned(c->x, 16) && aligned(c->x_new, 16) && aligned(c->g, 16) &&
+                     (!c->m || aligned(c->m, 16)) && (c->ld % 4 == 0);
+    StepGeom ge;
+    ge.x = c->x;
+    ge.x_new = c->x_new;
+    ge.m = c->m;
+    ge.g = c->g;
+    ge.ld = c->ld;
+    ge.n = c->n;
+    ge.lr = c->lr;
+    ge.mu = c->mu;
+    const int64_t nv = vec ? c->d / 4 : 0;
+    const int64_t tail = c->d - nv * 4;
+    hipError_t e = hipSuccess;
+    for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {
+        ge.col0 = pass == 0 ? 0 : nv * 4;
+        ge.ncols = pass == 0 ? nv : tail;
+        if (ge.ncols == 0) continue;
+        const int v = pass == 0 ? 4 : 1;
+        e = global ? launch_step_global(c, ge, v) : launch_step_walk(c, ge, mode, S, v);
+    }
+    if (e != hipSuccess) return hip_fail(c, e, "step kernel launch");
+    float* t = c->x;
+    c->x = c->x_new;
+    c->x_new = t;
+    c->k += 1;
+    return GPGA_OK;
+}
+
+gpga_status gpga_consensus_error(gpga_ctx* c, double* out_host) {
+    if (!c) return GPGA_EINVAL;
+    if (!out_host) return fail(c, GPGA_EINVAL, "out_host must not be NULL");
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    DeviceGuard guard(c->device);
+    gpga_status s = grow_f64(c, &c->partials, &c->partials_cap, consensus_partials_needed(c));
+    if (s != GPGA_OK) return s;
+    size_t need = 0;
+    hipError_t e = launch_consensus_sq(c, &need);
+    if (e != hipSuccess) return hip_fail(c, e, "consensus kernel launch");
+    e = hipMemcpyAsync(c->host_scalar, c->partials, sizeof(double), hipMemcpyDeviceToHost, c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipMemcpyAsync");
+    e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    *out_host = std::sqrt(*c->host_scalar);
+    return GPGA_OK;
+}
+
+gpga_status gpga_mean(gpga_ctx* c, float* xbar_dev) {
+    if (!c) return GPGA_EINVAL;
+    if (!xbar_dev || !aligned(xbar_dev, 4)) return fail(c, GPGA_EINVAL, "xbar_dev must be a 4-byte aligned device pointer");
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    DeviceGuard guard(c->device);
+    hipError_t e = launch_col_mean(c, xbar_dev);
+    if (e != hipSuccess) return hip_fail(c, e, "mean kernel launch");
+    return GPGA_OK;
+}
+
+gpga_status gpga_current_x(const gpga_ctx* c, float** x_dev_out) {
+    if (!c || !x_dev_out) return GPGA_EINVAL;
+    if (!c->bound) return GPGA_ESTATE;
+    *x_dev_out = c->x;
+    return GPGA_OK;
+}
+
+gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
+    if (!c || !name) return GPGA_EINVAL;
+    if (!strcmp(name, "unroll")) {
+        if (value != 0 && !is_pow2_le8(value)) return fail(c, GPGA_EINVAL, "unroll must be 0, 1, 2, 4 or 8");
+        c->opt_unroll = (int)value;
+    } else if (!strcmp(name, "waves")) {
+        if (value != 0 && !is_pow2_le8(value)) return fail(c, GPGA_EINVAL, "waves must be 0, 1, 2, 4 or 8");
+        if (value && c->opt_row_split > value) return fail(c, GPGA_EINVAL, "waves must be >= row_split");
+        c->opt_waves = (int)value;
+    } else if (!strcmp(name, "row_split")) {
+        if (value != 0 && !is_pow2_le8(value)) return fail(c, GPGA_EINVAL, "row_split must be 0, 1, 2, 4 or 8");
+        if (value > (c->opt_waves ? c->opt_waves : 4)) return fail(c, GPGA_EINVAL, "row_split must not exceed waves");
+        c->opt_row_split = (int)value;
+    } else if (!strcmp(name, "row_lanes")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4) return fail(c, GPGA_EINVAL, "row_lanes must be 0, 1, 2 or 4");
+        c->opt_row_lanes = (int)value;
+    } else if (!strcmp(name, "xcd_swizzle")) {
+        if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
+        c->opt_xcd_swizzle = (int)value;
+    } else {
+        return fail(c, GPGA_EINVAL, "unknown option '%s'", name);
+    }
+    return GPGA_OK;
+}
+
+const char* gpga_last_error(const gpga_ctx* c) { return c ? c->err : "null context"; }
+
+}  // extern "C"

@@ -1,0 +1,414 @@
+// Local stochastic gradients g_i = grad F_i(x_i; xi_i) for all n simulated nodes
+// (Algorithm 1, line 1 of the loop).  Three families:
+//
+//  * synthetic    G[i][c] = sigma * N(seed, TAG_GRAD, i, k, c): a counter-addressed
+//                 normal (Philox4x32-10 + Box-Muller) standing in for a network's
+//                 backward pass.  Integer/ALU bound; one 128-bit store per lane.
+//  * stored rows  least squares and logistic regression (Sec. 5.1 loss) on a
+//                 materialised n x M x d array: a batched GEMV pair per node,
+//                 (1) margins z_b = <row_b, x_i> -> per-sample coefficient,
+//                 (2) g_i = sum_b coef_b * row_b.  Plain FMA, no matrix cores: each
+//                 node has its own x_i, so there is no shared operand to tile.
+//  * virtual rows logistic regression whose feature rows are regenerated from
+//                 the counter RNG inside both passes (the array would not fit).
+#include "gpga_internal.hpp"
+
+namespace {
+
+// ---------------------------------------------------------------- counter RNG
+
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u;
+constexpr uint32_t kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u;
+constexpr uint32_t kPhiloxW1 = 0xBB67AE85u;
+
+constexpr uint32_t TAG_GRAD = 1u;
+constexpr uint32_t TAG_FEAT = 2u;
+constexpr uint32_t TAG_MU = 3u;
+
+struct u32x4 {
+    uint32_t a, b, c, d;
+};
+
+// Philox4x32 with 10 rounds (Salmon et al., SC'11): two 32x32->64 multiplies per
+// round, outputs permuted and xor-ed with the round key; key += Weyl constants.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(kPhiloxM0, c0), lo0 = kPhiloxM0 * c0;
+        const uint32_t hi1 = __umulhi(kPhiloxM1, c2), lo1 = kPhiloxM1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0;
+        c1 = lo1;
+        c2 = n2;
+        c3 = lo0;
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+    }
+    return {c0, c1, c2, c3};
+}
+
+// 32 random bits -> uniform in (0,1), exactly representable in fp32.
+__device__ __forceinline__ float uniform23(uint32_t r) {
+    return ((float)(r >> 9) + 0.5f) * 0x1p-23f;
+}
+
+// Four standard normals for one column quad: Box-Muller on (u0,u1) and (u2,u3).
+__device__ __forceinline__ v4f normals4(uint32_t c4, uint32_t a, uint32_t b, uint32_t tag,
+                                        uint32_t k0, uint32_t k1) {
+    const u32x4 r = philox4x32_10(c4, a, b, tag, k0, k1);
+    const float ra = sqrtf(-2.0f * logf(uniform23(r.a)));
+    const float rb = sqrtf(-2.0f * logf(uniform23(r.c)));
+    float sa, ca, sb, cb;
+    sincospif(2.0f * uniform23(r.b), &sa, &ca);
+    sincospif(2.0f * uniform23(r.d), &sb, &cb);
+    v4f z;
+    z.x = ra * ca;
+    z.y = ra * sa;
+    z.z = rb * cb;
+    z.w = rb * sb;
+    return z;
+}
+
+// ---------------------------------------------------------------- synthetic
+
+__global__ void __launch_bounds__(256) k_synth_grad(float* __restrict__ g, int64_t ld, int64_t d,
+                                                    uint32_t k0, uint32_t k1, uint32_t kiter,
+                                                    float sigma, int vec_ok) {
+    const int64_t c4 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t c = c4 * 4;
+    if (c >= d) return;
+    const uint32_t i = blockIdx.y;
+    const v4f z = sigma * normals4((uint32_t)c4, i, kiter, TAG_GRAD, k0, k1);
+    float* row = g + (int64_t)i * ld;
+    if (vec_ok && c + 3 < d) {
+        __builtin_nontemporal_store(z, reinterpret_cast<v4f*>(row + c));
+    } else {
+        row[c] = z.x;
+        if (c + 1 < d) row[c + 1] = z.y;
+        if (c + 2 < d) row[c + 2] = z.z;
+        if (c + 3 < d) row[c + 3] = z.w;
+    }
+}
+
+// ---------------------------------------------------------------- reductions
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;
+}
+
+// Sum over the workgroup; result valid in thread 0.
+__device__ __forceinline__ double block_sum(double v, double* s_buf) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) s_buf[wave] = v;
+    __syncthreads();
+    double t = 0.0;
+    if (threadIdx.x == 0)
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += s_buf[w];
+    return t;
+}
+
+// Per-sample coefficient and loss term from the margin z.
+//   least squares: r = z - b          coef = r / B           loss = r^2 / (2B)
+//   logistic     : t = y z            coef = -y s(-t) / B    loss = ln(1 + e^{-t}) / B
+template <int KIND>
+__device__ __forceinline__ void sample_terms(double z, float target, float invB, float* coef,
+                                             float* loss) {
+    if (KIND == PROB_LSQ) {
+        const double r = z - (double)target;
+        *coef = (float)(r * invB);
+        *loss = (float)(0.5 * r * r * invB);
+    } else {
+        const double t = (double)target * z;
+        const double e = exp(-fabs(t));               // in (0,1], never overflows
+        const double sig = (t >= 0.0) ? e / (1.0 + e) : 1.0 / (1.0 + e);   // sigma(-t)
+        *coef = (float)(-(double)target * sig * invB);
+        *loss = (float)((fmax(-t, 0.0) + log1p(e)) * invB);
+    }
+}
+
+// ---------------------------------------------------------------- stored rows
+
+// Pass 1: one workgroup per (sample slot b, node i): z = <row, x_i> in fp64.
+template <int KIND>
+__global__ void __launch_bounds__(256) k_rows_margin(const float* __restrict__ feat,
+                                                     const float* __restrict__ tgt,
+                                                     const float* __restrict__ x, int64_t ld,
+                                                     const int32_t* __restrict__ idx, int32_t B,
+                                                     int32_t M, int64_t d, int vec_ok,
+                                                     float* __restrict__ coef,
+                                                     float* __restrict__ lossterm) {
+    __shared__ double s_buf[4];
+    const int b = blockIdx.x, i = blockIdx.y;
+    const int32_t r = idx ? idx[(int64_t)i * B + b] : b;
+    const float* __restrict__ f = feat + ((int64_t)i * M + r) * d;
+    const float* __restrict__ xi = x + (int64_t)i * ld;
+    double acc = 0.0;
+    if (vec_ok) {
+        const int64_t d4 = d >> 2;
+        const v4f* f4 = reinterpret_cast<const v4f*>(f);
+        const v4f* x4 = reinterpret_cast<const v4f*>(xi);
+        for (int64_t c = threadIdx.x; c < d4; c += blockDim.x) {
+            const v4f fv = f4[c], xv = x4[c];
+            acc += (double)fv.x * xv.x + (double)fv.y * xv.y + (double)fv.z * xv.z +
+                   (double)fv.w * xv.w;
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < d; c += blockDim.x) acc += (double)f[c] * xi[c];
+    }
+    const double z = block_sum(acc, s_buf);
+    if (threadIdx.x == 0) {
+        float cf, ls;
+        sample_terms<KIND>(z, tgt[(int64_t)i * M + r], 1.0f / (float)B, &cf, &ls);
+        coef[(int64_t)i * B + b] = cf;
+        lossterm[(int64_t)i * B + b] = ls;
+    }
+}
+
+// Pass 2: one lane per column quad of node i: g = sum_b coef_b * row_b[c].
+__global__ void __launch_bounds__(256) k_rows_accum(const float* __restrict__ feat,
+                                                    const float* __restrict__ coef,
+                                                    const int32_t* __restrict__ idx, int32_t B,
+                                                    int32_t M, int64_t d, int vec_ok,
+                                                    float* __restrict__ g, int64_t ld) {
+    const int i = blockIdx.y;
+    const float* __restrict__ fi = feat + (int64_t)i * M * d;
+    const float* __restrict__ ci = coef + (int64_t)i * B;
+    const int32_t* __restrict__ ii = idx ? idx + (int64_t)i * B : nullptr;
+    float* __restrict__ gi = g + (int64_t)i * ld;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (vec_ok) {
+        if (t * 4 >= d) return;
+        double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+        for (int b = 0; b < B; ++b) {
+            const int32_t r = ii ? ii[b] : b;
+            const v4f fv = reinterpret_cast<const v4f*>(fi + (int64_t)r * d)[t];
+            const double cb = ci[b];
+            a0 += cb * fv.x;
+            a1 += cb * fv.y;
+            a2 += cb * fv.z;
+            a3 += cb * fv.w;
+        }
+        v4f out;
+        out.x = (float)a0;
+        out.y = (float)a1;
+        out.z = (float)a2;
+        out.w = (float)a3;
+        reinterpret_cast<v4f*>(gi)[t] = out;
+    } else {
+        if (t >= d) return;
+        double a0 = 0;
+        for (int b = 0; b < B; ++b) {
+            const int32_t r = ii ? ii[b] : b;
+            a0 += (double)ci[b] * fi[(int64_t)r * d + t];
+        }
+        gi[t] = (float)a0;
+    }
+}
+
+// loss[i] = sum_b lossterm[i][b]  (terms already carry the 1/B)
+__global__ void __launch_bounds__(256) k_loss_sum(const float* __restrict__ lossterm, int32_t B,
+                                                  float* __restrict__ loss) {
+    __shared__ double s_buf[4];
+    const int i = blockIdx.x;
+    double acc = 0.0;
+    for (int b = threadIdx.x; b < B; b += blockDim.x) acc += lossterm[(int64_t)i * B + b];
+    const double t = block_sum(acc, s_buf);
+    if (threadIdx.x == 0) loss[i] = (float)t;
+}
+
+// ---------------------------------------------------------------- virtual rows
+
+// Feature quad h_{i,m}[4c4 .. 4c4+3] = mu_i + zeta_{i,m}, rounded to fp32 like a
+// stored feature would be.
+__device__ __forceinline__ v4f virtual_quad(v4f mu, uint32_t c4, uint32_t i, uint32_t m,
+                                            uint32_t k0, uint32_t k1) {
+    return mu + normals4(c4, i, m, TAG_FEAT, k0, k1);
+}
+
+// Pass 1: grid (column chunks, node).  Each lane owns column quads and keeps B
+// partial margins; the node shift mu_i is generated once per quad and reused for
+// all B samples.  Partial margins are combined per workgroup and added into
+// zpart[i][b] (fp64 atomics: order-independent to well below fp32 resolution).
+template <int BMAX>
+__global__ void __launch_bounds__(256) k_virtual_margin(const float* __restrict__ x, int64_t ld,
+                                                        int64_t d, const int32_t* __restrict__ idx,
+                                                        int32_t B, uint32_t k0, uint32_t k1,
+                                                        float mu_sigma, int64_t quads_per_block,
+                                                        double* __restrict__ zpart) {
+    __shared__ double s_buf[4];
+    const uint32_t i = blockIdx.y;
+    const int64_t d4 = (d + 3) >> 2;
+    const int64_t q_begin = (int64_t)blockIdx.x * quads_per_block;
+    const int64_t q_end = (q_begin + quads_per_block < d4) ? q_begin + quads_per_block : d4;
+    const float* __restrict__ xi = x + (int64_t)i * ld;
+    double acc[BMAX];
+#pragma unroll
+    for (int b = 0; b < BMAX; ++b) acc[b] = 0.0;
+    for (int64_t q = q_begin + threadIdx.x; q < q_end; q += blockDim.x) {
+        const int64_t c = q * 4;
+        v4f xv;
+        xv.x = xi[c];
+        xv.y = (c + 1 < d) ? xi[c + 1] : 0.f;
+        xv.z = (c + 2 < d) ? xi[c + 2] : 0.f;
+        xv.w = (c + 3 < d) ? xi[c + 3] : 0.f;
+        const v4f mu = mu_sigma * normals4((uint32_t)q, i, 0u, TAG_MU, k0, k1);
+#pragma unroll
+        for (int b = 0; b < BMAX; ++b) {
+            if (b < B) {
+                const v4f h = virtual_quad(mu, (uint32_t)q, i, (uint32_t)idx[(int64_t)i * B + b], k0, k1);
+                acc[b] += (double)h.x * xv.x + (double)h.y * xv.y + (double)h.z * xv.z +
+                          (double)h.w * xv.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < BMAX; ++b) {
+        if (b < B) {
+            const double t = block_sum(acc[b], s_buf);
+            if (threadIdx.x == 0) atomicAdd(&zpart[(int64_t)i * B + b], t);
+            __syncthreads();
+        }
+    }
+}
+
+__global__ void k_virtual_coef(const double* __restrict__ zpart, const float* __restrict__ y,
+                               const int32_t* __restrict__ idx, int32_t B, int32_t M, int32_t n,
+                               float* __restrict__ coef, float* __restrict__ lossterm) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)n * B) return;
+    const int i = (int)(t / B);
+    float cf, ls;
+    sample_terms<PROB_LOGREG>(zpart[t], y[(int64_t)i * M + idx[t]], 1.0f / (float)B, &cf, &ls);
+    coef[t] = cf;
+    lossterm[t] = ls;
+}
+
+// Pass 2: one lane per column quad of node i, features regenerated.
+template <int BMAX>
+__global__ void __launch_bounds__(256) k_virtual_accum(const float* __restrict__ coef,
+                                                       const int32_t* __restrict__ idx, int32_t B,
+                                                       int64_t d, uint32_t k0, uint32_t k1,
+                                                       float mu_sigma, int vec_ok,
+                                                       float* __restrict__ g, int64_t ld) {
+    const uint32_t i = blockIdx.y;
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t c = q * 4;
+    if (c >= d) return;
+    const v4f mu = mu_sigma * normals4((uint32_t)q, i, 0u, TAG_MU, k0, k1);
+    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+#pragma unroll
+    for (int b = 0; b < BMAX; ++b) {
+        if (b < B) {
+            const v4f h = virtual_quad(mu, (uint32_t)q, i, (uint32_t)idx[(int64_t)i * B + b], k0, k1);
+            const double cb = coef[(int64_t)i * B + b];
+            a0 += cb * h.x;
+            a1 += cb * h.y;
+            a2 += cb * h.z;
+            a3 += cb * h.w;
+        }
+    }
+    float* row = g + (int64_t)i * ld;
+    if (vec_ok && c + 3 < d) {
+        v4f out;
+        out.x = (float)a0;
+        out.y = (float)a1;
+        out.z = (float)a2;
+        out.w = (float)a3;
+        *reinterpret_cast<v4f*>(row + c) = out;
+    } else {
+        row[c] = (float)a0;
+        if (c + 1 < d) row[c + 1] = (float)a1;
+        if (c + 2 < d) row[c + 2] = (float)a2;
+        if (c + 3 < d) row[c + 3] = (float)a3;
+    }
+}
+
+__global__ void k_zero_f64(double* p, int64_t count) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < count) p[t] = 0.0;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+hipError_t launch_synth_grad(const gpga_ctx* c) {
+    const int64_t d4 = (c->d + 3) / 4;
+    dim3 grid((unsigned)((d4 + 255) / 256), (unsigned)c->n), block(256);
+    const int vec_ok = aligned16(c->g) && (c->ld % 4 == 0);
+    hipLaunchKernelGGL(k_synth_grad, grid, block, 0, c->stream, c->g, c->ld, c->d,
+                       (uint32_t)(c->seed & 0xffffffffu), (uint32_t)(c->seed >> 32),
+                       (uint32_t)(c->k & 0xffffffff), c->grad_sigma, vec_ok);
+    return hipGetLastError();
+}
+
+hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out) {
+    const int32_t Beff = idx ? B : c->M;
+    float* coef = c->coef;
+    float* lossterm = c->coef + (size_t)c->n * Beff;
+    const int vec_feat = aligned16(c->feat) && (c->d % 4 == 0);
+    const int vec_x = vec_feat && aligned16(c->x) && (c->ld % 4 == 0);
+    dim3 grid1((unsigned)Beff, (unsigned)c->n), block(256);
+    if (c->problem == PROB_LSQ) {
+        hipLaunchKernelGGL((k_rows_margin<PROB_LSQ>), grid1, block, 0, c->stream, c->feat, c->tgt,
+                           c->x, c->ld, idx, Beff, c->M, c->d, vec_x, coef, lossterm);
+    } else {
+        hipLaunchKernelGGL((k_rows_margin<PROB_LOGREG>), grid1, block, 0, c->stream, c->feat,
+                           c->tgt, c->x, c->ld, idx, Beff, c->M, c->d, vec_x, coef, lossterm);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (loss_out) {
+        hipLaunchKernelGGL(k_loss_sum, dim3((unsigned)c->n), block, 0, c->stream, lossterm, Beff,
+                           loss_out);
+        return hipGetLastError();
+    }
+    const int vec_g = vec_feat && aligned16(c->g) && (c->ld % 4 == 0);
+    const int64_t cols = vec_g ? c->d / 4 : c->d;
+    dim3 grid2((unsigned)((cols + 255) / 256), (unsigned)c->n);
+    hipLaunchKernelGGL(k_rows_accum, grid2, block, 0, c->stream, c->feat, coef, idx, Beff, c->M,
+                       c->d, vec_g, c->g, c->ld);
+    return hipGetLastError();
+}
+
+hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out) {
+    constexpr int BMAX = 32;
+    if (B > BMAX) return hipErrorInvalidValue;
+    float* coef = c->coef;
+    float* lossterm = c->coef + (size_t)c->n * B;
+    double* zpart = c->partials;  // n*B doubles, sized by the caller
+    const uint32_t k0 = (uint32_t)(c->seed & 0xffffffffu), k1 = (uint32_t)(c->seed >> 32);
+    const int64_t nb = (int64_t)c->n * B;
+    hipLaunchKernelGGL(k_zero_f64, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, c->stream,
+                       zpart, nb);
+    const int64_t d4 = (c->d + 3) / 4;
+    // enough workgroups per node to fill the chip, at least 256 quads each
+    int64_t chunks = (4096 + c->n - 1) / c->n;
+    const int64_t max_chunks = (d4 + 255) / 256;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    const int64_t qpb = (d4 + chunks - 1) / chunks;
+    dim3 grid1((unsigned)((d4 + qpb - 1) / qpb), (unsigned)c->n), block(256);
+    hipLaunchKernelGGL((k_virtual_margin<BMAX>), grid1, block, 0, c->stream, c->x, c->ld, c->d, idx,
+                       B, k0, k1, c->mu_sigma, qpb, zpart);
+    hipLaunchKernelGGL(k_virtual_coef, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, c->stream,
+                       zpart, c->tgt, idx, B, c->M, c->n, coef, lossterm);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (loss_out) {
+        hipLaunchKernelGGL(k_loss_sum, dim3((unsigned)c->n), block, 0, c->stream, lossterm, B,
+                           loss_out);
+        return hipGetLastError();
+    }
+    const int vec_ok = aligned16(c->g) && (c->ld % 4 == 0);
+    dim3 grid2((unsigned)((d4 + 255) / 256), (unsigned)c->n);
+    hipLaunchKernelGGL((k_virtual_accum<BMAX>), grid2, block, 0, c->stream, coef, idx, B, c->d, k0,
+                       k1, c->mu_sigma, vec_ok, c->g, c->ld);
+    return hipGetLastError();
+}

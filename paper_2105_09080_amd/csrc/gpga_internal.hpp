@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of libgpga.
+// Host-side context, launch descriptors and the launcher entry points of each
+// kernel family.  Nothing here is part of the public ABI (include/gpga.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gpga.h"
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;  // gfx950 wavefront width
+
+enum GpgaProblem : int { PROB_NONE = 0, PROB_LSQ, PROB_LOGREG, PROB_LOGREG_VIRTUAL, PROB_SYNTH };
+
+// Mixing stencil along a walk over rows.
+enum StencilMode : int {
+    MODE_RING = 0,  // (prev + cur + next) / 3
+    MODE_PEER = 1,  // (cur + next) / 2
+    MODE_SELF = 2   // cur
+};
+
+struct gpga_ctx {
+    int32_t n = 0;
+    int64_t d = 0;
+    int32_t topo = 0;
+    int64_t H = 0;
+    float lr = 0.f, mu = 0.f;
+    int64_t k = 0;
+    int device = 0;
+
+    // bound buffers (borrowed)
+    float* x = nullptr;      // live iterates
+    float* x_new = nullptr;  // target of the next step
+    float* m = nullptr;
+    float* g = nullptr;
+    int64_t ld = 0;
+    hipStream_t stream = nullptr;
+    bool bound = false;
+
+    // attached problem (borrowed data)
+    int problem = PROB_NONE;
+    const float* feat = nullptr;  // A or features, n x M x d
+    const float* tgt = nullptr;   // b or labels, n x M
+    int32_t M = 0;
+    uint64_t seed = 0;
+    float grad_sigma = 0.f;  // sqrt(grad_var)
+    float mu_sigma = 0.f;    // sqrt(mu_var)
+
+    // library-owned scratch
+    float* coef = nullptr;  // n x B per-sample coefficients / margins
+    size_t coef_cap = 0;    // in floats
+    double* partials = nullptr;
+    size_t partials_cap = 0;  // in doubles
+    double* host_scalar = nullptr;  // pinned, 1 double
+
+    // launch geometry overrides (0 = automatic)
+    int opt_unroll = 0;
+    int opt_waves = 0;
+    int opt_row_split = 0;
+    int opt_row_lanes = 0;
+    int opt_xcd_swizzle = 0;
+
+    char err[256] = {0};
+};
+
+// Description of one fused step launch over columns [col0, col0 + ncols*V).
+struct StepGeom {
+    const float* x;
+    float* x_new;
+    float* m;
+    const float* g;
+    int64_t ld;     // floats
+    int64_t col0;   // first column of this pass (floats)
+    int64_t ncols;  // columns of this pass in units of the vector type
+    int32_t n;
+    float lr, mu;
+};
+
+// ---- launchers (each returns hipSuccess or the launch error) ----------------
+
+// Gossip step: stencil `mode` along cycles of the row permutation i -> (i+S) mod n.
+hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec);
+// Global-average step.
+hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec);
+
+// Gradients.
+hipError_t launch_synth_grad(const gpga_ctx* c);
+hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
+hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
+
+// Reductions and fills.
+hipError_t launch_fill_rows(const gpga_ctx* c, float* dst, const float* row_or_null);
+hipError_t launch_col_mean(const gpga_ctx* c, float* xbar);
+// Sum of squared deviations into c->partials[0] (device double).
+hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed);
+size_t consensus_partials_needed(const gpga_ctx* c);

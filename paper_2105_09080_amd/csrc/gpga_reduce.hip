@@ -1,0 +1,221 @@
+// Column reductions over the node axis and row fills.
+//
+//  * node mean       xbar = (1/n) sum_i x_i                       (App. A notation)
+//  * consensus error ||X - 1 xbar^T||_F^2 = sum_c sum_i (x_ic - xbar_c)^2
+//                    (the consensus distance of Sec. 4 / App. B)
+//  * fill            every row <- one d-vector (Algorithm 1: all x_i^(0) equal)
+//
+// Both reductions read X exactly once (4 B per element).  The consensus error
+// uses the shifted one-pass form with row 0 as the shift:
+//     d_i = x_i - x_0 ;  sum_i (x_i - xbar)^2 = sum_i d_i^2 - (sum_i d_i)^2 / n
+// with d_i formed in fp32 (exact or nearly so when rows are close) and both
+// sums carried in fp64, so the subtraction never loses the small quantity the
+// method is about.  Column results are reduced with a wavefront shuffle, an LDS
+// step across waves and one partial per workgroup; a last single-workgroup
+// kernel adds the partials in a fixed order (bitwise reproducible).
+#include "gpga_internal.hpp"
+
+namespace {
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p) {
+    return __builtin_nontemporal_load(p);
+}
+
+struct d4 {
+    double x, y, z, w;
+};
+__device__ __forceinline__ void acc_add(double& a, float v) { a += (double)v; }
+__device__ __forceinline__ void acc_add(d4& a, v4f v) {
+    a.x += (double)v.x;
+    a.y += (double)v.y;
+    a.z += (double)v.z;
+    a.w += (double)v.w;
+}
+__device__ __forceinline__ void acc_sq(double& a, float v) { a += (double)v * (double)v; }
+__device__ __forceinline__ void acc_sq(d4& a, v4f v) {
+    a.x += (double)v.x * v.x;
+    a.y += (double)v.y * v.y;
+    a.z += (double)v.z * v.z;
+    a.w += (double)v.w * v.w;
+}
+__device__ __forceinline__ float to_mean(double a, double inv_n) { return (float)(a * inv_n); }
+__device__ __forceinline__ v4f to_mean(const d4& a, double inv_n) {
+    v4f r;
+    r.x = (float)(a.x * inv_n);
+    r.y = (float)(a.y * inv_n);
+    r.z = (float)(a.z * inv_n);
+    r.w = (float)(a.w * inv_n);
+    return r;
+}
+__device__ __forceinline__ double col_ss(double s1, double s2, double inv_n) {
+    const double v = s2 - s1 * s1 * inv_n;
+    return v > 0.0 ? v : 0.0;
+}
+__device__ __forceinline__ double col_ss(const d4& s1, const d4& s2, double inv_n) {
+    return col_ss(s1.x, s2.x, inv_n) + col_ss(s1.y, s2.y, inv_n) + col_ss(s1.z, s2.z, inv_n) +
+           col_ss(s1.w, s2.w, inv_n);
+}
+
+template <typename T>
+struct AccOf;
+template <>
+struct AccOf<float> {
+    typedef double type;
+    __device__ static double zero() { return 0.0; }
+};
+template <>
+struct AccOf<v4f> {
+    typedef d4 type;
+    __device__ static d4 zero() { return {0.0, 0.0, 0.0, 0.0}; }
+};
+
+constexpr int U = 4;
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_col_mean(const float* __restrict__ x, int64_t ld,
+                                                  int64_t col0, int64_t ncols, int32_t n,
+                                                  float* __restrict__ xbar) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    const int64_t col = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (col >= ncols) return;
+    const int64_t ldT = ld / V;
+    const T* __restrict__ xp = reinterpret_cast<const T*>(x + col0) + col;
+    typename AccOf<T>::type acc = AccOf<T>::zero();
+    for (int base = 0; base < n; base += U) {
+        T v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u < n) v[u] = ld_stream(xp + (int64_t)(base + u) * ldT);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u < n) acc_add(acc, v[u]);
+    }
+    reinterpret_cast<T*>(xbar + col0)[col] = to_mean(acc, 1.0 / (double)n);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_consensus(const float* __restrict__ x, int64_t ld,
+                                                   int64_t col0, int64_t ncols, int32_t n,
+                                                   double* __restrict__ partials) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    __shared__ double s_buf[4];
+    const int64_t col = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    double ss = 0.0;
+    if (col < ncols) {
+        const int64_t ldT = ld / V;
+        const T* __restrict__ xp = reinterpret_cast<const T*>(x + col0) + col;
+        const T x0 = xp[0];
+        typename AccOf<T>::type s1 = AccOf<T>::zero(), s2 = AccOf<T>::zero();
+        for (int base = 1; base < n; base += U) {
+            T v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (base + u < n) v[u] = ld_stream(xp + (int64_t)(base + u) * ldT);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (base + u < n) {
+                    const T dlt = v[u] - x0;
+                    acc_add(s1, dlt);
+                    acc_sq(s2, dlt);
+                }
+        }
+        ss = col_ss(s1, s2, 1.0 / (double)n);
+    }
+    ss = wave_sum(ss);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) s_buf[wave] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (s_buf[0] + s_buf[1]) + (s_buf[2] + s_buf[3]);
+}
+
+// out[0] = sum of `count` partials, one workgroup, fixed order.
+__global__ void __launch_bounds__(256) k_final_sum(const double* __restrict__ partials,
+                                                   int64_t count, double* __restrict__ out) {
+    __shared__ double s_buf[4];
+    double acc = 0.0;
+    for (int64_t t = threadIdx.x; t < count; t += blockDim.x) acc += partials[t];
+    acc = wave_sum(acc);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) s_buf[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = (s_buf[0] + s_buf[1]) + (s_buf[2] + s_buf[3]);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_fill_rows(float* __restrict__ dst, int64_t ld,
+                                                   int64_t col0, int64_t ncols, int32_t n,
+                                                   const float* __restrict__ src) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    const int64_t col = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (col >= ncols) return;
+    const int64_t ldT = ld / V;
+    const T v = src ? reinterpret_cast<const T*>(src + col0)[col] : T(0);
+    T* __restrict__ dp = reinterpret_cast<T*>(dst + col0) + col;
+    for (int row = 0; row < n; ++row) dp[(int64_t)row * ldT] = v;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+size_t consensus_partials_needed(const gpga_ctx* c) {
+    // vector pass workgroups + scalar tail workgroup + 1 result slot
+    return (size_t)((c->d / 4 + 255) / 256) + (size_t)((c->d + 255) / 256) + 2;
+}
+
+hipError_t launch_fill_rows(const gpga_ctx* c, float* dst, const float* src) {
+    const bool vec = aligned16(dst) && (!src || aligned16(src)) && (c->ld % 4 == 0);
+    const int64_t nv = vec ? c->d / 4 : 0;
+    if (nv > 0) {
+        hipLaunchKernelGGL((k_fill_rows<v4f>), dim3((unsigned)((nv + 255) / 256)), dim3(256), 0,
+                           c->stream, dst, c->ld, (int64_t)0, nv, c->n, src);
+    }
+    const int64_t tail = c->d - nv * 4;
+    if (tail > 0) {
+        hipLaunchKernelGGL((k_fill_rows<float>), dim3((unsigned)((tail + 255) / 256)), dim3(256), 0,
+                           c->stream, dst, c->ld, nv * 4, tail, c->n, src);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_col_mean(const gpga_ctx* c, float* xbar) {
+    const bool vec = aligned16(c->x) && aligned16(xbar) && (c->ld % 4 == 0);
+    const int64_t nv = vec ? c->d / 4 : 0;
+    if (nv > 0) {
+        hipLaunchKernelGGL((k_col_mean<v4f>), dim3((unsigned)((nv + 255) / 256)), dim3(256), 0,
+                           c->stream, c->x, c->ld, (int64_t)0, nv, c->n, xbar);
+    }
+    const int64_t tail = c->d - nv * 4;
+    if (tail > 0) {
+        hipLaunchKernelGGL((k_col_mean<float>), dim3((unsigned)((tail + 255) / 256)), dim3(256), 0,
+                           c->stream, c->x, c->ld, nv * 4, tail, c->n, xbar);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
+    *partials_needed = consensus_partials_needed(c);
+    if (c->partials_cap < *partials_needed) return hipErrorOutOfMemory;
+    const bool vec = aligned16(c->x) && (c->ld % 4 == 0);
+    const int64_t nv = vec ? c->d / 4 : 0;
+    const int64_t tail = c->d - nv * 4;
+    const int64_t b1 = (nv + 255) / 256, b2 = (tail + 255) / 256;
+    double* parts = c->partials + 1;  // slot 0 holds the result
+    if (b1 > 0) {
+        hipLaunchKernelGGL((k_consensus<v4f>), dim3((unsigned)b1), dim3(256), 0, c->stream, c->x,
+                           c->ld, (int64_t)0, nv, c->n, parts);
+    }
+    if (b2 > 0) {
+        hipLaunchKernelGGL((k_consensus<float>), dim3((unsigned)b2), dim3(256), 0, c->stream, c->x,
+                           c->ld, nv * 4, tail, c->n, parts + b1);
+    }
+    hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(256), 0, c->stream, parts, b1 + b2, c->partials);
+    return hipGetLastError();
+}

@@ -1,0 +1,424 @@
+// Fused Gossip-PGA step kernels for gfx950 (Algorithm 1, lines 2-6 of the
+// paper's listing in Sec. 3; matrix form in App. A):
+//
+//     m_i <- mu*m_i + g_i ;  y_i = x_i - gamma*m_i              (local update)
+//     gossip :  x_new_i = sum_j w_ij y_j                         (W_k sparse)
+//     global :  x_new_i = (1/n) sum_j y_j                        (every H-th step)
+//
+// The node axis (rows) is the only axis along which elements interact, so a
+// lane owns one 128-bit column group (4 fp32 columns) and *walks down rows*.
+// Lanes of a wavefront sit on consecutive column groups: every access of a wave
+// is one fully coalesced 1 KiB row segment.  Each element of x, m, g is read
+// from HBM exactly once per step and each element of m, x_new written once.
+//
+// Gossip ("walk") kernel.  Both graphs are stencils along cycles of the row
+// permutation i -> (i + S) mod n:
+//   ring      S = 1      one cycle of length n, taps (prev, cur, next)/3
+//   one-peer  S = 2^s    gcd(S,n) cycles of length n/gcd, taps (cur, next)/2
+//   W = I     -          n cycles of length 1, tap cur
+// A "walker" is one wavefront walking a contiguous segment of one cycle with
+// the last two y values kept in registers.  When a cycle is split over Q
+// wavefronts of a workgroup (few columns, many rows) the first/last y of every
+// segment are staged through LDS, so neighbour rows are never re-read from HBM.
+//
+// Global-average kernel.  Rows are spread over (row lanes of a wave) x (waves
+// of the workgroup); partial column sums are combined with a wavefront
+// shuffle (xor butterfly) and then an LDS tree across waves.  Every row gets
+// the same bits of the mean, so the rows are bit-identical afterwards.
+#include "gpga_internal.hpp"
+
+namespace {
+
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p) {
+    return __builtin_nontemporal_load(p);
+}
+template <typename T>
+__device__ __forceinline__ void st_stream(T* p, T v) {
+    __builtin_nontemporal_store(v, p);
+}
+
+__device__ __forceinline__ float shfl_xor_t(float v, int off) { return __shfl_xor(v, off, kWave); }
+__device__ __forceinline__ v4f shfl_xor_t(v4f v, int off) {
+    v4f r;
+    r.x = __shfl_xor(v.x, off, kWave);
+    r.y = __shfl_xor(v.y, off, kWave);
+    r.z = __shfl_xor(v.z, off, kWave);
+    r.w = __shfl_xor(v.w, off, kWave);
+    return r;
+}
+
+constexpr int kMaxWaves = 8;
+
+struct WalkArgs {
+    StepGeom ge;
+    int32_t S;    // row stride of the permutation
+    int32_t C;    // number of cycles
+    int32_t L;    // cycle length
+    int32_t Q;    // segments (wavefronts) per cycle
+    int32_t tpb;  // column tiles per workgroup
+    int32_t xcd;  // remap blockIdx.x so that an XCD sees contiguous tiles
+    int64_t gx;   // logical grid size in x
+};
+
+// blockIdx.x -> logical tile-group index.  Hardware hands consecutive workgroup
+// ids to the 8 XCDs round-robin; with the remap each XCD walks a contiguous
+// range of column tiles (its own L2 and the fabric then see sequential
+// streams).
+__device__ __forceinline__ int64_t logical_block(int64_t bid, int64_t gx, int xcd) {
+    if (!xcd) return bid;
+    const int64_t per = gx >> 3;          // groups per XCD (floor)
+    const int64_t main_part = per << 3;   // blocks covered by the regular part
+    if (bid >= main_part) return bid;     // ragged tail keeps its identity
+    return (bid & 7) * per + (bid >> 3);
+}
+
+template <typename T, int MODE, bool MOM, int U>
+__global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    __shared__ T s_first[kMaxWaves][kWave];
+    __shared__ T s_last[kMaxWaves][kWave];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform -> SGPR
+    const int waves = blockDim.x >> 6;
+    const int wpb = waves / a.tpb;  // walkers per workgroup
+    const int tile_l = wave / wpb;
+    const int walk_l = wave - tile_l * wpb;
+    const int64_t bx = logical_block(blockIdx.x, a.gx, a.xcd);
+    const int64_t tile = bx * a.tpb + tile_l;
+    const int walker = blockIdx.y * wpb + walk_l;
+    const int64_t col = tile * kWave + lane;
+    const bool on = (walker < a.C * a.Q) && (col < a.ge.ncols);
+
+    const int cyc = walker / a.Q;
+    const int seg = walker - cyc * a.Q;
+    const int p0 = (int)(((int64_t)seg * a.L) / a.Q);
+    const int p1 = (int)(((int64_t)(seg + 1) * a.L) / a.Q);
+    const int len = p1 - p0;
+    const int n = a.ge.n;
+    const int S = a.S;
+    int row = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
+
+    const int64_t ldT = a.ge.ld / V;
+    const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+    const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+    T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+    T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+    const float lr = a.ge.lr, mu = a.ge.mu;
+    const float third = 1.0f / 3.0f;
+
+    T yf = T(0), ys = T(0), pp = T(0), pc = T(0);
+    const int row_first = row;
+    int row_prev = row;
+
+    if (on) {
+        for (int base = 0; base < len; base += U) {
+            T xv[U], mv[U], gv[U];
+            int rw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                rw[u] = row;
+                if (base + u < len) {
+                    const int64_t off = (int64_t)row * ldT;
+                    xv[u] = ld_stream(xp + off);
+                    if (MOM) mv[u] = ld_stream(mp + off);
+                    gv[u] = ld_stream(gp + off);
+                    row += S;
+                    if (row >= n) row -= n;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (base + u < len) {
+                    T mom = gv[u];
+                    if (MOM) {
+                        mom = mu * mv[u] + gv[u];
+                        st_stream(mp + (int64_t)rw[u] * ldT, mom);
+                    }
+                    const T y = xv[u] - lr * mom;
+                    const int idx = base + u;
+                    if (idx == 0) yf = y;
+                    if (idx == 1) ys = y;
+                    if (MODE == MODE_RING) {
+                        if (idx >= 2) st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + y) * third);
+                    } else if (MODE == MODE_PEER) {
+                        if (idx >= 1) st_stream(xnp + (int64_t)row_prev * ldT, (pc + y) * 0.5f);
+                    } else {
+                        st_stream(xnp + (int64_t)rw[u] * ldT, y);
+                    }
+                    pp = pc;
+                    pc = y;
+                    row_prev = rw[u];
+                }
+            }
+        }
+    }
+    if (MODE == MODE_SELF) return;
+
+    // Close the stencil at the two ends of the segment.  One walker per cycle:
+    // the cycle closes on itself.  Q walkers per cycle: neighbours' boundary
+    // y values come through LDS.
+    T left = pc, right = yf;
+    if (a.Q > 1) {
+        s_first[wave][lane] = yf;
+        s_last[wave][lane] = pc;
+        __syncthreads();
+        const int w0 = wave - seg;
+        left = s_last[w0 + (seg + a.Q - 1) % a.Q][lane];
+        right = s_first[w0 + (seg + 1) % a.Q][lane];
+    }
+    if (on) {
+        if (MODE == MODE_RING) {
+            if (len == 1) {
+                st_stream(xnp + (int64_t)row_first * ldT, (left + yf + right) * third);
+            } else {
+                st_stream(xnp + (int64_t)row_first * ldT, (left + yf + ys) * third);
+                st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + right) * third);
+            }
+        } else {  // MODE_PEER: last row of the segment pairs with the next segment's first
+            st_stream(xnp + (int64_t)row_prev * ldT, (pc + right) * 0.5f);
+        }
+    }
+}
+
+struct GlobalArgs {
+    StepGeom ge;
+    int32_t RL;   // lanes of a wave spread over rows (1, 2, 4)
+    int32_t tpb;  // column tiles per workgroup
+    int32_t xcd;
+    int64_t gx;
+    float inv_n;
+};
+
+template <typename T, bool MOM, int U>
+__global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalArgs a) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    __shared__ T s_part[kMaxWaves][kWave];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform -> SGPR
+    const int waves = blockDim.x >> 6;
+    const int wpb = waves / a.tpb;  // waves sharing one column tile
+    const int tile_l = wave / wpb;
+    const int wrow = wave - tile_l * wpb;
+    const int CL = kWave / a.RL;  // column lanes per wave
+    const int lane_c = lane & (CL - 1);
+    const int lane_r = lane / CL;
+    const int64_t bx = logical_block(blockIdx.x, a.gx, a.xcd);
+    const int64_t tile = bx * a.tpb + tile_l;
+    const int64_t col = tile * CL + lane_c;
+    const bool on = col < a.ge.ncols;
+    const int n = a.ge.n;
+    const int RS = a.RL * wpb;            // row splitters per column
+    const int r0 = wrow * a.RL + lane_r;  // this lane's first row
+
+    const int64_t ldT = a.ge.ld / V;
+    const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+    const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+    T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+    T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+    const float lr = a.ge.lr, mu = a.ge.mu;
+
+    T sum = T(0);
+    if (on) {
+        for (int base = r0; base < n; base += RS * U) {
+            T xv[U], mv[U], gv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = base + u * RS;
+                if (row < n) {
+                    const int64_t off = (int64_t)row * ldT;
+                    xv[u] = ld_stream(xp + off);
+                    if (MOM) mv[u] = ld_stream(mp + off);
+                    gv[u] = ld_stream(gp + off);
+                }
+            }
+            T part = T(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = base + u * RS;
+                if (row < n) {
+                    T mom = gv[u];
+                    if (MOM) {
+                        mom = mu * mv[u] + gv[u];
+                        st_stream(mp + (int64_t)row * ldT, mom);
+                    }
+                    part += xv[u] - lr * mom;
+                }
+            }
+            sum += part;
+        }
+    }
+    // wavefront shuffle across the row lanes (xor butterfly: all lanes end equal)
+    for (int off = CL; off < kWave; off <<= 1) sum += shfl_xor_t(sum, off);
+    // LDS tree across the waves that share this column tile
+    if (wpb > 1) {
+        if (lane_r == 0) s_part[wave][lane_c] = sum;
+        __syncthreads();
+        const int w0 = tile_l * wpb;
+        for (int stride = 1; stride < wpb; stride <<= 1) {
+            if (lane_r == 0 && (wrow & (2 * stride - 1)) == 0 && wrow + stride < wpb)
+                s_part[wave][lane_c] += s_part[wave + stride][lane_c];
+            __syncthreads();
+        }
+        sum = s_part[w0][lane_c];
+    }
+    const T mean = sum * a.inv_n;
+    if (on) {
+        for (int base = r0; base < n; base += RS * U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = base + u * RS;
+                if (row < n) st_stream(xnp + (int64_t)row * ldT, mean);
+            }
+        }
+    }
+}
+
+int gcd_i(int a, int b) {
+    while (b) {
+        int t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
+}
+int pow2_floor(int v) {
+    int p = 1;
+    while (p * 2 <= v) p *= 2;
+    return p;
+}
+int pow2_ceil(int v) {
+    int p = 1;
+    while (p < v) p *= 2;
+    return p;
+}
+
+template <typename T, int MODE, bool MOM>
+hipError_t launch_walk_u(int U, dim3 grid, dim3 block, hipStream_t st, const WalkArgs& a) {
+    switch (U) {
+        case 1: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 1>), grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 2>), grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 8>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 4>), grid, block, 0, st, a); break;
+    }
+    return hipGetLastError();
+}
+
+template <typename T, bool MOM>
+hipError_t launch_walk_mode(int mode, int U, dim3 grid, dim3 block, hipStream_t st,
+                            const WalkArgs& a) {
+    switch (mode) {
+        case MODE_RING: return launch_walk_u<T, MODE_RING, MOM>(U, grid, block, st, a);
+        case MODE_PEER: return launch_walk_u<T, MODE_PEER, MOM>(U, grid, block, st, a);
+        default: return launch_walk_u<T, MODE_SELF, MOM>(U, grid, block, st, a);
+    }
+}
+
+template <typename T, bool MOM>
+hipError_t launch_global_u(int U, dim3 grid, dim3 block, hipStream_t st, const GlobalArgs& a) {
+    switch (U) {
+        case 1: hipLaunchKernelGGL((k_step_global<T, MOM, 1>), grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((k_step_global<T, MOM, 2>), grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL((k_step_global<T, MOM, 8>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((k_step_global<T, MOM, 4>), grid, block, 0, st, a); break;
+    }
+    return hipGetLastError();
+}
+
+// Waves in flight that saturate the chip: 256 CUs x 4 SIMDs x a few waves each.
+constexpr int64_t kEnoughWaves = 16384;
+
+}  // namespace
+
+hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec) {
+    if (ge.ncols <= 0) return hipSuccess;
+    const int n = ge.n;
+    WalkArgs a;
+    a.ge = ge;
+    if (mode == MODE_SELF) {
+        a.S = 0;
+        a.C = n;
+        a.L = 1;
+    } else {
+        a.S = S;
+        a.C = gcd_i(S, n);
+        a.L = n / a.C;
+    }
+    const int waves = c->opt_waves ? c->opt_waves : 4;
+    const int U = c->opt_unroll ? c->opt_unroll : 4;
+    const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
+
+    int Q = 1;
+    if (mode != MODE_SELF) {
+        if (c->opt_row_split) {
+            Q = c->opt_row_split;
+        } else if (tiles * a.C < kEnoughWaves) {
+            Q = pow2_floor(a.L / 4 > 0 ? a.L / 4 : 1);  // keep segments of >= 4 rows
+        }
+        if (Q > waves) Q = waves;
+        if (Q > a.L) Q = pow2_floor(a.L);
+    }
+    a.Q = Q;
+    int wpb = pow2_ceil((int)((int64_t)a.C * Q > waves ? waves : a.C * Q));
+    if (wpb > waves) wpb = waves;
+    if (wpb < Q) wpb = Q;
+    a.tpb = waves / wpb;
+    const int64_t gx = (tiles + a.tpb - 1) / a.tpb;
+    const int64_t gy = ((int64_t)a.C * Q + wpb - 1) / wpb;
+    if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
+    a.gx = gx;
+    a.xcd = c->opt_xcd_swizzle;
+    dim3 grid((unsigned)gx, (unsigned)gy), block(kWave * waves);
+    const bool mom = c->mu != 0.f;
+    if (vec == 4) {
+        return mom ? launch_walk_mode<v4f, true>(mode, U, grid, block, c->stream, a)
+                   : launch_walk_mode<v4f, false>(mode, U, grid, block, c->stream, a);
+    }
+    return mom ? launch_walk_mode<float, true>(mode, U, grid, block, c->stream, a)
+               : launch_walk_mode<float, false>(mode, U, grid, block, c->stream, a);
+}
+
+hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
+    if (ge.ncols <= 0) return hipSuccess;
+    const int n = ge.n;
+    GlobalArgs a;
+    a.ge = ge;
+    a.inv_n = 1.0f / (float)n;
+    const int waves = c->opt_waves ? c->opt_waves : 4;
+    const int U = c->opt_unroll ? c->opt_unroll : 4;
+
+    // Spread rows over lanes and waves only when columns alone cannot fill the chip.
+    const int64_t tiles64 = (ge.ncols + kWave - 1) / kWave;
+    int RL = 1, wpb = 1;
+    if (c->opt_row_lanes) {
+        RL = c->opt_row_lanes;
+    } else if (tiles64 < kEnoughWaves / 8) {
+        RL = 4;
+    }
+    while (RL > 1 && RL > n) RL >>= 1;
+    if (c->opt_row_split) {
+        wpb = c->opt_row_split;
+    } else if (tiles64 * RL < kEnoughWaves) {
+        wpb = pow2_floor(n / (4 * RL) > 0 ? n / (4 * RL) : 1);
+    }
+    if (wpb > waves) wpb = waves;
+    while (wpb > 1 && RL * wpb > n) wpb >>= 1;
+    a.RL = RL;
+    a.tpb = waves / wpb;
+    const int CL = kWave / RL;
+    const int64_t tiles = (ge.ncols + CL - 1) / CL;
+    const int64_t gx = (tiles + a.tpb - 1) / a.tpb;
+    if (gx > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.gx = gx;
+    a.xcd = c->opt_xcd_swizzle;
+    dim3 grid((unsigned)gx), block(kWave * waves);
+    const bool mom = c->mu != 0.f;
+    if (vec == 4) {
+        return mom ? launch_global_u<v4f, true>(U, grid, block, c->stream, a)
+                   : launch_global_u<v4f, false>(U, grid, block, c->stream, a);
+    }
+    return mom ? launch_global_u<float, true>(U, grid, block, c->stream, a)
+               : launch_global_u<float, false>(U, grid, block, c->stream, a);
+}
