@@ -44,11 +44,15 @@ def parse_args():
     ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1",
                     help="comma list of extra workload:topology pairs measured after the primary ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0,
+                    help="run this many plain device copies of one n x d buffer before the timed loop "
+                         "(a kernel of known size: reads and writes 4*n*d bytes; used to scale rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--opt", action="append", default=[], help="launch option name=value (repeatable)")
     return ap.parse_args()
 
 
-def run_workload(cfg_name, topology, steps, warmup, opts):
+def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0):
     """Times `steps` passes of local_grad + step.  Returns a dict of measurements."""
     import torch
 
@@ -71,6 +75,8 @@ def run_workload(cfg_name, topology, steps, warmup, opts):
         grad = lambda: sim.local_grad(idx[sim.k])
 
     with torch.cuda.stream(stream):
+        for _ in range(copy_probe):
+            sim._bufs[1].copy_(sim._bufs[0])
         for _ in range(warmup):
             grad()
             sim.step()
@@ -173,7 +179,7 @@ def main():
         opts[name] = int(v)
 
     topo = args.topology or inputs.CONFIGS[args.config]["topologies"][0]
-    main_res = run_workload(args.config, topo, args.steps, args.warmup, opts)
+    main_res = run_workload(args.config, topo, args.steps, args.warmup, opts, args.copy_probe)
     others = []
     for item in [s for s in args.also.split(",") if s]:
         name, tp = item.split(":")

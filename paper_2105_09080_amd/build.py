@@ -31,7 +31,8 @@ def hipcc_path() -> str:
 
 def build_library(verbose: bool = True) -> str:
     """Compile all HIP sources into paper_2105_09080_amd/libgpga.so and return its path."""
-    cmd = [hipcc_path(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    extra = os.environ.get("GPGA_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)

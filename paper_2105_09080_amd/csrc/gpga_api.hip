@@ -161,6 +161,9 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
         delete c;
         return GPGA_EDEVICE;
     }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
+        c->num_cus = cus;
     const size_t need = consensus_partials_needed(c);
     if (hipMalloc(reinterpret_cast<void**>(&c->partials), need * sizeof(double)) != hipSuccess) {
         delete c;
@@ -404,6 +407,12 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "xcd_swizzle")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
         c->opt_xcd_swizzle = (int)value;
+    } else if (!strcmp(name, "pace")) {
+        if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "pace must be 0 or 1");
+        c->opt_pace = (int)value;
+    } else if (!strcmp(name, "blocks_per_cu")) {
+        if (value < -1 || value > 32) return fail(c, GPGA_EINVAL, "blocks_per_cu must be -1 (automatic), 0 (off) or 1..32");
+        c->opt_blocks_per_cu = (int)value;
     } else {
         return fail(c, GPGA_EINVAL, "unknown option '%s'", name);
     }

@@ -61,6 +61,9 @@ struct gpga_ctx {
     int opt_row_split = 0;
     int opt_row_lanes = 0;
     int opt_xcd_swizzle = 0;
+    int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
+    int num_cus = 256;
+    int opt_pace = 0;
 
     char err[256] = {0};
 };

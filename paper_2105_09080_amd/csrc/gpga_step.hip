@@ -29,13 +29,27 @@
 
 namespace {
 
+#ifndef GPGA_NT_LOAD
+#define GPGA_NT_LOAD 1
+#endif
+#ifndef GPGA_NT_STORE
+#define GPGA_NT_STORE 1
+#endif
 template <typename T>
 __device__ __forceinline__ T ld_stream(const T* p) {
+#if GPGA_NT_LOAD
     return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
 }
 template <typename T>
 __device__ __forceinline__ void st_stream(T* p, T v) {
+#if GPGA_NT_STORE
     __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
 }
 
 __device__ __forceinline__ float shfl_xor_t(float v, int off) { return __shfl_xor(v, off, kWave); }
@@ -49,6 +63,7 @@ __device__ __forceinline__ v4f shfl_xor_t(v4f v, int off) {
 }
 
 constexpr int kMaxWaves = 8;
+constexpr int kDefaultBlocksPerCu = 0;
 
 struct WalkArgs {
     StepGeom ge;
@@ -58,6 +73,7 @@ struct WalkArgs {
     int32_t Q;    // segments (wavefronts) per cycle
     int32_t tpb;  // column tiles per workgroup
     int32_t xcd;  // remap blockIdx.x so that an XCD sees contiguous tiles
+    int32_t pace; // barrier after every row batch
     int64_t gx;   // logical grid size in x
 };
 
@@ -85,11 +101,8 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     const int wpb = waves / a.tpb;  // walkers per workgroup
     const int tile_l = wave / wpb;
     const int walk_l = wave - tile_l * wpb;
-    const int64_t bx = logical_block(blockIdx.x, a.gx, a.xcd);
-    const int64_t tile = bx * a.tpb + tile_l;
     const int walker = blockIdx.y * wpb + walk_l;
-    const int64_t col = tile * kWave + lane;
-    const bool on = (walker < a.C * a.Q) && (col < a.ge.ncols);
+    const bool walker_on = walker < a.C * a.Q;
 
     const int cyc = walker / a.Q;
     const int seg = walker - cyc * a.Q;
@@ -98,86 +111,102 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     const int len = p1 - p0;
     const int n = a.ge.n;
     const int S = a.S;
-    int row = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
-
+    const int row_first = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
     const int64_t ldT = a.ge.ld / V;
-    const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
-    const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
-    T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
-    T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
     const float lr = a.ge.lr, mu = a.ge.mu;
     const float third = 1.0f / 3.0f;
 
-    T yf = T(0), ys = T(0), pp = T(0), pc = T(0);
-    const int row_first = row;
-    int row_prev = row;
+    // Grid-stride over column-tile groups.  With a grid sized to the resident
+    // workgroups of the chip (persistent launch) all wavefronts start row 0 of
+    // their tile together and stay in step, so at any moment the whole chip
+    // streams a few rows of x, m, g over a wide contiguous column window
+    // instead of touching all n rows of every array at once.
+    for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
+        const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
+        const int64_t col = tile * kWave + lane;
+        const bool on = walker_on && (col < a.ge.ncols);
 
-    if (on) {
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+
+        T yf = T(0), ys = T(0), pp = T(0), pc = T(0);
+        int row = row_first;
+        int row_prev = row;
+
         for (int base = 0; base < len; base += U) {
-            T xv[U], mv[U], gv[U];
-            int rw[U];
+            if (on) {
+                T xv[U], mv[U], gv[U];
+                int rw[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                rw[u] = row;
-                if (base + u < len) {
-                    const int64_t off = (int64_t)row * ldT;
-                    xv[u] = ld_stream(xp + off);
-                    if (MOM) mv[u] = ld_stream(mp + off);
-                    gv[u] = ld_stream(gp + off);
-                    row += S;
-                    if (row >= n) row -= n;
+                for (int u = 0; u < U; ++u) {
+                    rw[u] = row;
+                    if (base + u < len) {
+                        const int64_t off = (int64_t)row * ldT;
+                        xv[u] = ld_stream(xp + off);
+                        if (MOM) mv[u] = ld_stream(mp + off);
+                        gv[u] = ld_stream(gp + off);
+                        row += S;
+                        if (row >= n) row -= n;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (base + u < len) {
+                        T mom = gv[u];
+                        if (MOM) {
+                            mom = mu * mv[u] + gv[u];
+                            st_stream(mp + (int64_t)rw[u] * ldT, mom);
+                        }
+                        const T y = xv[u] - lr * mom;
+                        const int idx = base + u;
+                        if (idx == 0) yf = y;
+                        if (idx == 1) ys = y;
+                        if (MODE == MODE_RING) {
+                            if (idx >= 2) st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + y) * third);
+                        } else if (MODE == MODE_PEER) {
+                            if (idx >= 1) st_stream(xnp + (int64_t)row_prev * ldT, (pc + y) * 0.5f);
+                        } else {
+                            st_stream(xnp + (int64_t)rw[u] * ldT, y);
+                        }
+                        pp = pc;
+                        pc = y;
+                        row_prev = rw[u];
+                    }
                 }
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (base + u < len) {
-                    T mom = gv[u];
-                    if (MOM) {
-                        mom = mu * mv[u] + gv[u];
-                        st_stream(mp + (int64_t)rw[u] * ldT, mom);
-                    }
-                    const T y = xv[u] - lr * mom;
-                    const int idx = base + u;
-                    if (idx == 0) yf = y;
-                    if (idx == 1) ys = y;
-                    if (MODE == MODE_RING) {
-                        if (idx >= 2) st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + y) * third);
-                    } else if (MODE == MODE_PEER) {
-                        if (idx >= 1) st_stream(xnp + (int64_t)row_prev * ldT, (pc + y) * 0.5f);
-                    } else {
-                        st_stream(xnp + (int64_t)rw[u] * ldT, y);
-                    }
-                    pp = pc;
-                    pc = y;
-                    row_prev = rw[u];
-                }
-            }
+            // Optional workgroup-wide pacing: all wavefronts of the workgroup move
+            // down the rows together (host enables it only when every wavefront of
+            // the workgroup has the same trip count).
+            if (a.pace) __syncthreads();
         }
-    }
-    if (MODE == MODE_SELF) return;
+        if (MODE == MODE_SELF) continue;
 
-    // Close the stencil at the two ends of the segment.  One walker per cycle:
-    // the cycle closes on itself.  Q walkers per cycle: neighbours' boundary
-    // y values come through LDS.
-    T left = pc, right = yf;
-    if (a.Q > 1) {
-        s_first[wave][lane] = yf;
-        s_last[wave][lane] = pc;
-        __syncthreads();
-        const int w0 = wave - seg;
-        left = s_last[w0 + (seg + a.Q - 1) % a.Q][lane];
-        right = s_first[w0 + (seg + 1) % a.Q][lane];
-    }
-    if (on) {
-        if (MODE == MODE_RING) {
-            if (len == 1) {
-                st_stream(xnp + (int64_t)row_first * ldT, (left + yf + right) * third);
-            } else {
-                st_stream(xnp + (int64_t)row_first * ldT, (left + yf + ys) * third);
-                st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + right) * third);
+        // Close the stencil at the two ends of the segment.  One walker per
+        // cycle: the cycle closes on itself.  Q walkers per cycle: neighbours'
+        // boundary y values come through LDS.
+        T left = pc, right = yf;
+        if (a.Q > 1) {
+            s_first[wave][lane] = yf;
+            s_last[wave][lane] = pc;
+            __syncthreads();
+            const int w0 = wave - seg;
+            left = s_last[w0 + (seg + a.Q - 1) % a.Q][lane];
+            right = s_first[w0 + (seg + 1) % a.Q][lane];
+            __syncthreads();  // LDS is rewritten by the next tile group
+        }
+        if (on) {
+            if (MODE == MODE_RING) {
+                if (len == 1) {
+                    st_stream(xnp + (int64_t)row_first * ldT, (left + yf + right) * third);
+                } else {
+                    st_stream(xnp + (int64_t)row_first * ldT, (left + yf + ys) * third);
+                    st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + right) * third);
+                }
+            } else {  // MODE_PEER: last row of the segment pairs with the next segment's first
+                st_stream(xnp + (int64_t)row_prev * ldT, (pc + right) * 0.5f);
             }
-        } else {  // MODE_PEER: last row of the segment pairs with the next segment's first
-            st_stream(xnp + (int64_t)row_prev * ldT, (pc + right) * 0.5f);
         }
     }
 }
@@ -205,72 +234,75 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     const int CL = kWave / a.RL;  // column lanes per wave
     const int lane_c = lane & (CL - 1);
     const int lane_r = lane / CL;
-    const int64_t bx = logical_block(blockIdx.x, a.gx, a.xcd);
-    const int64_t tile = bx * a.tpb + tile_l;
-    const int64_t col = tile * CL + lane_c;
-    const bool on = col < a.ge.ncols;
     const int n = a.ge.n;
     const int RS = a.RL * wpb;            // row splitters per column
     const int r0 = wrow * a.RL + lane_r;  // this lane's first row
-
     const int64_t ldT = a.ge.ld / V;
-    const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
-    const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
-    T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
-    T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
     const float lr = a.ge.lr, mu = a.ge.mu;
 
-    T sum = T(0);
-    if (on) {
-        for (int base = r0; base < n; base += RS * U) {
-            T xv[U], mv[U], gv[U];
+    for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
+        const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
+        const int64_t col = tile * CL + lane_c;
+        const bool on = col < a.ge.ncols;
+
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+
+        T sum = T(0);
+        if (on) {
+            for (int base = r0; base < n; base += RS * U) {
+                T xv[U], mv[U], gv[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = base + u * RS;
-                if (row < n) {
-                    const int64_t off = (int64_t)row * ldT;
-                    xv[u] = ld_stream(xp + off);
-                    if (MOM) mv[u] = ld_stream(mp + off);
-                    gv[u] = ld_stream(gp + off);
-                }
-            }
-            T part = T(0);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = base + u * RS;
-                if (row < n) {
-                    T mom = gv[u];
-                    if (MOM) {
-                        mom = mu * mv[u] + gv[u];
-                        st_stream(mp + (int64_t)row * ldT, mom);
+                for (int u = 0; u < U; ++u) {
+                    const int row = base + u * RS;
+                    if (row < n) {
+                        const int64_t off = (int64_t)row * ldT;
+                        xv[u] = ld_stream(xp + off);
+                        if (MOM) mv[u] = ld_stream(mp + off);
+                        gv[u] = ld_stream(gp + off);
                     }
-                    part += xv[u] - lr * mom;
                 }
-            }
-            sum += part;
-        }
-    }
-    // wavefront shuffle across the row lanes (xor butterfly: all lanes end equal)
-    for (int off = CL; off < kWave; off <<= 1) sum += shfl_xor_t(sum, off);
-    // LDS tree across the waves that share this column tile
-    if (wpb > 1) {
-        if (lane_r == 0) s_part[wave][lane_c] = sum;
-        __syncthreads();
-        const int w0 = tile_l * wpb;
-        for (int stride = 1; stride < wpb; stride <<= 1) {
-            if (lane_r == 0 && (wrow & (2 * stride - 1)) == 0 && wrow + stride < wpb)
-                s_part[wave][lane_c] += s_part[wave + stride][lane_c];
-            __syncthreads();
-        }
-        sum = s_part[w0][lane_c];
-    }
-    const T mean = sum * a.inv_n;
-    if (on) {
-        for (int base = r0; base < n; base += RS * U) {
+                T part = T(0);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = base + u * RS;
-                if (row < n) st_stream(xnp + (int64_t)row * ldT, mean);
+                for (int u = 0; u < U; ++u) {
+                    const int row = base + u * RS;
+                    if (row < n) {
+                        T mom = gv[u];
+                        if (MOM) {
+                            mom = mu * mv[u] + gv[u];
+                            st_stream(mp + (int64_t)row * ldT, mom);
+                        }
+                        part += xv[u] - lr * mom;
+                    }
+                }
+                sum += part;
+            }
+        }
+        // wavefront shuffle across the row lanes (xor butterfly: all lanes end equal)
+        for (int off = CL; off < kWave; off <<= 1) sum += shfl_xor_t(sum, off);
+        // LDS tree across the waves that share this column tile
+        if (wpb > 1) {
+            if (lane_r == 0) s_part[wave][lane_c] = sum;
+            __syncthreads();
+            const int w0 = tile_l * wpb;
+            for (int stride = 1; stride < wpb; stride <<= 1) {
+                if (lane_r == 0 && (wrow & (2 * stride - 1)) == 0 && wrow + stride < wpb)
+                    s_part[wave][lane_c] += s_part[wave + stride][lane_c];
+                __syncthreads();
+            }
+            sum = s_part[w0][lane_c];
+            __syncthreads();  // LDS is rewritten by the next tile group
+        }
+        const T mean = sum * a.inv_n;
+        if (on) {
+            for (int base = r0; base < n; base += RS * U) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int row = base + u * RS;
+                    if (row < n) st_stream(xnp + (int64_t)row * ldT, mean);
+                }
             }
         }
     }
@@ -330,6 +362,17 @@ hipError_t launch_global_u(int U, dim3 grid, dim3 block, hipStream_t st, const G
 // Waves in flight that saturate the chip: 256 CUs x 4 SIMDs x a few waves each.
 constexpr int64_t kEnoughWaves = 16384;
 
+// Workgroups launched along x.  Persistent launch: as many as are resident at
+// once (CUs x workgroups per CU), each striding over the tile groups, which
+// keeps all wavefronts on the same few rows at the same time.
+int64_t persistent_grid_x(const gpga_ctx* c, int64_t gx, int64_t gy) {
+    const int bpc = c->opt_blocks_per_cu < 0 ? kDefaultBlocksPerCu : c->opt_blocks_per_cu;
+    if (bpc == 0) return gx;
+    int64_t resident = ((int64_t)c->num_cus * bpc) / (gy > 0 ? gy : 1);
+    if (resident < 1) resident = 1;
+    return gx < resident ? gx : resident;
+}
+
 }  // namespace
 
 hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec) {
@@ -370,7 +413,10 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
     a.gx = gx;
     a.xcd = c->opt_xcd_swizzle;
-    dim3 grid((unsigned)gx, (unsigned)gy), block(kWave * waves);
+    // pacing needs identical trip counts in every wavefront of a workgroup
+    a.pace = (c->opt_pace && (a.L % Q == 0) && (((int64_t)a.C * Q) % wpb == 0)) ? 1 : 0;
+    const int64_t launch_x = persistent_grid_x(c, gx, gy);
+    dim3 grid((unsigned)launch_x, (unsigned)gy), block(kWave * waves);
     const bool mom = c->mu != 0.f;
     if (vec == 4) {
         return mom ? launch_walk_mode<v4f, true>(mode, U, grid, block, c->stream, a)
@@ -413,7 +459,8 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     if (gx > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.gx = gx;
     a.xcd = c->opt_xcd_swizzle;
-    dim3 grid((unsigned)gx), block(kWave * waves);
+    const int64_t launch_x = persistent_grid_x(c, gx, 1);
+    dim3 grid((unsigned)launch_x), block(kWave * waves);
     const bool mom = c->mu != 0.f;
     if (vec == 4) {
         return mom ? launch_global_u<v4f, true>(U, grid, block, c->stream, a)

@@ -107,6 +107,8 @@ OPTION_SETS = [
     {"waves": 8, "row_split": 8}, {"row_split": 1}, {"row_split": 2}, {"row_split": 4},
     {"row_lanes": 1, "row_split": 1}, {"row_lanes": 2}, {"row_lanes": 4, "row_split": 4},
     {"xcd_swizzle": 1}, {"xcd_swizzle": 1, "waves": 2, "row_split": 2},
+    {"blocks_per_cu": 1}, {"blocks_per_cu": 2, "waves": 2, "row_split": 2}, {"blocks_per_cu": 1, "xcd_swizzle": 1},
+    {"pace": 1}, {"pace": 1, "waves": 8, "blocks_per_cu": 1}, {"pace": 1, "row_split": 4},
 ]
 
 
