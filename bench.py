@@ -31,7 +31,9 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 # HBM bytes per launch of the fused gossip step measured with rocprofv3 --pmc
 # (FETCH_SIZE run + WRITE_SIZE run, scaled by a copy kernel of known size); the
 # summaries live under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "cfg3/ring": 32768038263,   # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
+}
 
 
 def parse_args():
