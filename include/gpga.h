@@ -157,8 +157,7 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * wavefront spread over rows: 0 = automatic, 1, 2, 4), "xcd_swizzle" (0/1),
  * "blocks_per_cu" (persistent launch of the fused step: -1 = automatic, 0 = one
  * workgroup per column-tile group, k = 1..32 resident workgroups per compute unit,
- * each striding over the tile groups), "pace" (0/1: the wavefronts of a workgroup
- * move down the rows together, one workgroup barrier per row batch). */
+ * each striding over the tile groups). */
 gpga_status gpga_set_option(gpga_ctx* ctx, const char* name, int64_t value);
 
 const char* gpga_last_error(const gpga_ctx* ctx);

@@ -63,6 +63,13 @@ __device__ __forceinline__ v4f shfl_xor_t(v4f v, int off) {
 }
 
 constexpr int kMaxWaves = 8;
+
+// Offset (in units of the vector type) of logical column group `col` in row 0.
+// Node-major: the column itself.  Panel layout: panels of 64 column groups, the
+// n rows of a panel adjacent in memory: [panel][row][64].
+__device__ __forceinline__ int64_t lane_offset(int64_t col, int panel, int n) {
+    return panel ? (col >> 6) * ((int64_t)n * kWave) + (col & (kWave - 1)) : col;
+}
 constexpr int kDefaultBlocksPerCu = 0;
 
 struct WalkArgs {
@@ -73,7 +80,6 @@ struct WalkArgs {
     int32_t Q;    // segments (wavefronts) per cycle
     int32_t tpb;  // column tiles per workgroup
     int32_t xcd;  // remap blockIdx.x so that an XCD sees contiguous tiles
-    int32_t pace; // barrier after every row batch
     int64_t gx;   // logical grid size in x
 };
 
@@ -112,7 +118,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     const int n = a.ge.n;
     const int S = a.S;
     const int row_first = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
-    const int64_t ldT = a.ge.ld / V;
+    const int64_t ldT = a.ge.panel ? kWave : a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
     const float third = 1.0f / 3.0f;
 
@@ -125,61 +131,115 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
         const int64_t col = tile * kWave + lane;
         const bool on = walker_on && (col < a.ge.ncols);
+        const int64_t coff = lane_offset(col, a.ge.panel, n);
 
-        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
-        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
-        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
-        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + coff;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + coff;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + coff : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + coff;
 
         T yf = T(0), ys = T(0), pp = T(0), pc = T(0);
         int row = row_first;
         int row_prev = row;
 
-        for (int base = 0; base < len; base += U) {
-            if (on) {
-                T xv[U], mv[U], gv[U];
-                int rw[U];
+        // One row: issue its three loads / turn loaded values into y (and store m).
+        auto load_row = [&](T& xv, T& mv, T& gv, int& rw) {
+            rw = row;
+            const int64_t off = (int64_t)row * ldT;
+            xv = ld_stream(xp + off);
+            if (MOM) mv = ld_stream(mp + off);
+            gv = ld_stream(gp + off);
+            row += S;
+            if (row >= n) row -= n;
+        };
+        auto y_of = [&](const T& xv, const T& mv, const T& gv, int rw) -> T {
+            T mom = gv;
+            if (MOM) {
+                mom = mu * mv + gv;
+                st_stream(mp + (int64_t)rw * ldT, mom);
+            }
+            return xv - lr * mom;
+        };
+        // Steady state (third row of the segment onwards): the new y completes the
+        // stencil of the previous row.
+        auto emit = [&](const T& y, int rw) {
+            if (MODE == MODE_RING) st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + y) * third);
+            if (MODE == MODE_PEER) st_stream(xnp + (int64_t)row_prev * ldT, (pc + y) * 0.5f);
+            pp = pc;
+            pc = y;
+            row_prev = rw;
+        };
+        struct Batch {
+            T xv[U], mv[U], gv[U];
+            int rw[U];
+        };
+        auto load_full = [&](Batch& b) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    rw[u] = row;
-                    if (base + u < len) {
-                        const int64_t off = (int64_t)row * ldT;
-                        xv[u] = ld_stream(xp + off);
-                        if (MOM) mv[u] = ld_stream(mp + off);
-                        gv[u] = ld_stream(gp + off);
-                        row += S;
-                        if (row >= n) row -= n;
-                    }
-                }
+            for (int u = 0; u < U; ++u) load_row(b.xv[u], b.mv[u], b.gv[u], b.rw[u]);
+        };
+        auto process_full = [&](const Batch& b) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (base + u < len) {
-                        T mom = gv[u];
-                        if (MOM) {
-                            mom = mu * mv[u] + gv[u];
-                            st_stream(mp + (int64_t)rw[u] * ldT, mom);
-                        }
-                        const T y = xv[u] - lr * mom;
-                        const int idx = base + u;
-                        if (idx == 0) yf = y;
-                        if (idx == 1) ys = y;
-                        if (MODE == MODE_RING) {
-                            if (idx >= 2) st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + y) * third);
-                        } else if (MODE == MODE_PEER) {
-                            if (idx >= 1) st_stream(xnp + (int64_t)row_prev * ldT, (pc + y) * 0.5f);
-                        } else {
-                            st_stream(xnp + (int64_t)rw[u] * ldT, y);
-                        }
-                        pp = pc;
-                        pc = y;
-                        row_prev = rw[u];
-                    }
+            for (int u = 0; u < U; ++u) emit(y_of(b.xv[u], b.mv[u], b.gv[u], b.rw[u]), b.rw[u]);
+        };
+
+        if (on) {
+            // First two rows of the segment: they only start the stencil window.
+            {
+                T x0, m0, g0, x1, m1, g1;
+                int r0 = 0, r1 = 0;
+                load_row(x0, m0, g0, r0);
+                if (len >= 2) load_row(x1, m1, g1, r1);
+                yf = y_of(x0, m0, g0, r0);
+                if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r0 * ldT, yf);
+                pc = yf;
+                row_prev = r0;
+                if (len >= 2) {
+                    ys = y_of(x1, m1, g1, r1);
+                    if (MODE == MODE_PEER) st_stream(xnp + (int64_t)r0 * ldT, (yf + ys) * 0.5f);
+                    if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r1 * ldT, ys);
+                    pp = yf;
+                    pc = ys;
+                    row_prev = r1;
                 }
             }
-            // Optional workgroup-wide pacing: all wavefronts of the workgroup move
-            // down the rows together (host enables it only when every wavefront of
-            // the workgroup has the same trip count).
-            if (a.pace) __syncthreads();
+            // Software-pipelined steady state over full batches of U rows.  The
+            // loads of the next batch are issued BEFORE the stores of the current
+            // one: a wavefront's memory operations retire in order, so a wait for
+            // those loads never includes the slower write acknowledgements of the
+            // stores behind them.  The hot loop is branch-free so that the wait
+            // counts stay exact.
+            const int rem = len > 2 ? len - 2 : 0;
+            const int nfull = rem / U;
+            const int tail = rem - nfull * U;
+            Batch A, B;
+            if (nfull >= 1) {
+                load_full(A);
+                int b = 0;
+                for (; b + 3 <= nfull; b += 2) {
+                    load_full(B);
+                    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: loads, then stores
+                    process_full(A);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_full(A);
+                    __builtin_amdgcn_sched_barrier(0);
+                    process_full(B);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (nfull - b == 2) {
+                    load_full(B);
+                    __builtin_amdgcn_sched_barrier(0);
+                    process_full(A);
+                    process_full(B);
+                } else {
+                    process_full(A);
+                }
+            }
+            for (int t = 0; t < tail; ++t) {
+                T xv, mv, gv;
+                int rw;
+                load_row(xv, mv, gv, rw);
+                emit(y_of(xv, mv, gv, rw), rw);
+            }
         }
         if (MODE == MODE_SELF) continue;
 
@@ -237,18 +297,19 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     const int n = a.ge.n;
     const int RS = a.RL * wpb;            // row splitters per column
     const int r0 = wrow * a.RL + lane_r;  // this lane's first row
-    const int64_t ldT = a.ge.ld / V;
+    const int64_t ldT = a.ge.panel ? kWave : a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
 
     for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
         const int64_t col = tile * CL + lane_c;
         const bool on = col < a.ge.ncols;
+        const int64_t coff = lane_offset(col, a.ge.panel, n);
 
-        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
-        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
-        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
-        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + coff;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + coff;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + coff : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + coff;
 
         T sum = T(0);
         if (on) {
@@ -413,8 +474,6 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
     a.gx = gx;
     a.xcd = c->opt_xcd_swizzle;
-    // pacing needs identical trip counts in every wavefront of a workgroup
-    a.pace = (c->opt_pace && (a.L % Q == 0) && (((int64_t)a.C * Q) % wpb == 0)) ? 1 : 0;
     const int64_t launch_x = persistent_grid_x(c, gx, gy);
     dim3 grid((unsigned)launch_x, (unsigned)gy), block(kWave * waves);
     const bool mom = c->mu != 0.f;

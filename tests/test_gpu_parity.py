@@ -108,7 +108,7 @@ OPTION_SETS = [
     {"row_lanes": 1, "row_split": 1}, {"row_lanes": 2}, {"row_lanes": 4, "row_split": 4},
     {"xcd_swizzle": 1}, {"xcd_swizzle": 1, "waves": 2, "row_split": 2},
     {"blocks_per_cu": 1}, {"blocks_per_cu": 2, "waves": 2, "row_split": 2}, {"blocks_per_cu": 1, "xcd_swizzle": 1},
-    {"pace": 1}, {"pace": 1, "waves": 8, "blocks_per_cu": 1}, {"pace": 1, "row_split": 4},
+    {"waves": 8, "blocks_per_cu": 1}, {"unroll": 1, "row_split": 4}, {"unroll": 2, "row_split": 2},
 ]
 
 
