@@ -332,7 +332,6 @@ gpga_status gpga_step(gpga_ctx* c) {
     ge.m = c->m;
     ge.g = c->g;
     ge.ld = c->ld;
-    ge.panel = (c->opt_panel && vec && c->d % 256 == 0 && c->ld == c->d) ? 1 : 0;
     ge.n = c->n;
     ge.lr = c->lr;
     ge.mu = c->mu;
@@ -408,9 +407,6 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "xcd_swizzle")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
         c->opt_xcd_swizzle = (int)value;
-    } else if (!strcmp(name, "panel")) {
-        if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "panel must be 0 or 1");
-        c->opt_panel = (int)value;
     } else if (!strcmp(name, "blocks_per_cu")) {
         if (value < -1 || value > 32) return fail(c, GPGA_EINVAL, "blocks_per_cu must be -1 (automatic), 0 (off) or 1..32");
         c->opt_blocks_per_cu = (int)value;

@@ -63,7 +63,6 @@ struct gpga_ctx {
     int opt_xcd_swizzle = 0;
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
-    int opt_panel = 0;
 
     char err[256] = {0};
 };
@@ -75,7 +74,6 @@ struct StepGeom {
     float* m;
     const float* g;
     int64_t ld;     // floats
-    int32_t panel;  // 1: column-panel layout [d/256][n][256] (128-bit path only)
     int64_t col0;   // first column of this pass (floats)
     int64_t ncols;  // columns of this pass in units of the vector type
     int32_t n;

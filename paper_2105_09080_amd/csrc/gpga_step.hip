@@ -63,14 +63,8 @@ __device__ __forceinline__ v4f shfl_xor_t(v4f v, int off) {
 }
 
 constexpr int kMaxWaves = 8;
-
-// Offset (in units of the vector type) of logical column group `col` in row 0.
-// Node-major: the column itself.  Panel layout: panels of 64 column groups, the
-// n rows of a panel adjacent in memory: [panel][row][64].
-__device__ __forceinline__ int64_t lane_offset(int64_t col, int panel, int n) {
-    return panel ? (col >> 6) * ((int64_t)n * kWave) + (col & (kWave - 1)) : col;
-}
 constexpr int kDefaultBlocksPerCu = 0;
+constexpr int kDefaultUnroll = 2;  // rows per batch; two batches are in flight (software pipeline)
 
 struct WalkArgs {
     StepGeom ge;
@@ -118,7 +112,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     const int n = a.ge.n;
     const int S = a.S;
     const int row_first = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
-    const int64_t ldT = a.ge.panel ? kWave : a.ge.ld / V;  // row stride in units of T
+    const int64_t ldT = a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
     const float third = 1.0f / 3.0f;
 
@@ -131,7 +125,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
         const int64_t col = tile * kWave + lane;
         const bool on = walker_on && (col < a.ge.ncols);
-        const int64_t coff = lane_offset(col, a.ge.panel, n);
+        const int64_t coff = col;
 
         const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + coff;
         const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + coff;
@@ -297,14 +291,14 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     const int n = a.ge.n;
     const int RS = a.RL * wpb;            // row splitters per column
     const int r0 = wrow * a.RL + lane_r;  // this lane's first row
-    const int64_t ldT = a.ge.panel ? kWave : a.ge.ld / V;  // row stride in units of T
+    const int64_t ldT = a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
 
     for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
         const int64_t col = tile * CL + lane_c;
         const bool on = col < a.ge.ncols;
-        const int64_t coff = lane_offset(col, a.ge.panel, n);
+        const int64_t coff = col;
 
         const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + coff;
         const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + coff;
@@ -451,7 +445,7 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
         a.L = n / a.C;
     }
     const int waves = c->opt_waves ? c->opt_waves : 4;
-    const int U = c->opt_unroll ? c->opt_unroll : 4;
+    const int U = c->opt_unroll ? c->opt_unroll : kDefaultUnroll;
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
 
     int Q = 1;
