@@ -33,6 +33,7 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 # summaries live under profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
     "cfg3/ring": 32768038263,   # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
+    "cfg4/expo1": 140800205238,  # profiles/step_cfg4_expo1.md
 }
 
 
