@@ -157,7 +157,11 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * wavefront spread over rows: 0 = automatic, 1, 2, 4), "xcd_swizzle" (0/1),
  * "blocks_per_cu" (persistent launch of the fused step: -1 = automatic, 0 = one
  * workgroup per column-tile group, k = 1..32 resident workgroups per compute unit,
- * each striding over the tile groups). */
+ * each striding over the tile groups), "pace_gbs" (target rate in GB/s of paced
+ * persistent launches: -1 = automatic, 0 = free running; paced wavefronts issue
+ * each row batch no earlier than a common start time plus the time the whole
+ * launch needs for the rows before it at that rate, which keeps the chip
+ * streaming a few rows at a time). */
 gpga_status gpga_set_option(gpga_ctx* ctx, const char* name, int64_t value);
 
 const char* gpga_last_error(const gpga_ctx* ctx);

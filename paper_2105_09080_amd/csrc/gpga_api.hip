@@ -164,12 +164,21 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
         c->num_cus = cus;
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && khz > 0)
+        c->clock_hz = 1e3 * (double)khz;
     const size_t need = consensus_partials_needed(c);
     if (hipMalloc(reinterpret_cast<void**>(&c->partials), need * sizeof(double)) != hipSuccess) {
         delete c;
         return GPGA_ENOMEM;
     }
     c->partials_cap = need;
+    if (hipMalloc(reinterpret_cast<void**>(&c->pace_slots), 64 * sizeof(unsigned long long)) == hipSuccess) {
+        (void)hipMemset(c->pace_slots, 0, 64 * sizeof(unsigned long long));
+        (void)hipDeviceSynchronize();
+    } else {
+        c->pace_slots = nullptr;
+    }
     if (hipHostMalloc(reinterpret_cast<void**>(&c->host_scalar), sizeof(double), hipHostMallocDefault) !=
         hipSuccess) {
         (void)hipFree(c->partials);
@@ -187,6 +196,7 @@ gpga_status gpga_destroy(gpga_ctx* c) {
     if (c->bound && hipStreamSynchronize(c->stream) != hipSuccess) s = GPGA_EDEVICE;
     if (c->coef) (void)hipFree(c->coef);
     if (c->partials) (void)hipFree(c->partials);
+    if (c->pace_slots) (void)hipFree(c->pace_slots);
     if (c->host_scalar) (void)hipHostFree(c->host_scalar);
     delete c;
     return s;
@@ -407,6 +417,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "xcd_swizzle")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
         c->opt_xcd_swizzle = (int)value;
+    } else if (!strcmp(name, "pace_gbs")) {
+        if (value < -1 || value > 16000) return fail(c, GPGA_EINVAL, "pace_gbs must be -1 (automatic), 0 (off) or a rate up to 16000 GB/s");
+        c->opt_pace_gbs = (int)value;
     } else if (!strcmp(name, "blocks_per_cu")) {
         if (value < -1 || value > 32) return fail(c, GPGA_EINVAL, "blocks_per_cu must be -1 (automatic), 0 (off) or 1..32");
         c->opt_blocks_per_cu = (int)value;

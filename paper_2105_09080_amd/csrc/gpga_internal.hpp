@@ -63,6 +63,10 @@ struct gpga_ctx {
     int opt_xcd_swizzle = 0;
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
+    int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
+    uint32_t pace_seq = 0;   // sequence number of paced launches
+    double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
+    unsigned long long* pace_slots = nullptr;  // 64 device words, library-owned
 
     char err[256] = {0};
 };

@@ -63,8 +63,14 @@ __device__ __forceinline__ v4f shfl_xor_t(v4f v, int off) {
 }
 
 constexpr int kMaxWaves = 8;
-constexpr int kDefaultBlocksPerCu = 0;
 constexpr int kDefaultUnroll = 2;  // rows per batch; two batches are in flight (software pipeline)
+
+// Pacing of a persistent launch (see pace_begin / pace_wait below).
+struct PaceArgs {
+    unsigned long long* slots;  // 64 start-time words, one per launch sequence number mod 64
+    uint32_t seq;               // launch sequence number
+    uint32_t unit_fp;           // clock counts (x 256) per 4-byte stream row of the whole launch; 0 = off
+};
 
 struct WalkArgs {
     StepGeom ge;
@@ -73,8 +79,10 @@ struct WalkArgs {
     int32_t L;    // cycle length
     int32_t Q;    // segments (wavefronts) per cycle
     int32_t tpb;  // column tiles per workgroup
-    int32_t xcd;  // remap blockIdx.x so that an XCD sees contiguous tiles
-    int64_t gx;   // logical grid size in x
+    int32_t xcd;  // remap tile groups so that an XCD sees contiguous tiles
+    int64_t gx;   // tile groups
+    int64_t gy;   // walker groups; work items = gx * gy, tile group fastest
+    PaceArgs pace;
 };
 
 // blockIdx.x -> logical tile-group index.  Hardware hands consecutive workgroup
@@ -89,6 +97,43 @@ __device__ __forceinline__ int64_t logical_block(int64_t bid, int64_t gx, int xc
     return (bid & 7) * per + (bid >> 3);
 }
 
+// Deadline pacing of a persistent launch.  Measured on this chip: a 3-read /
+// 2-write stream mix runs at 6.3-6.5 TB/s when the whole chip streams one row
+// of each array at a time, and drops to the 5.1-5.2 TB/s of a scattered copy
+// once >= 32 different rows are open at once - which is what free-running
+// walkers drift into, since each is at a different row of its own tile.
+// Pacing keeps them together without exchanging data: all wavefronts share
+// one start time t0 (the first workgroup to arrive publishes the chip's
+// constant-rate clock with a compare-and-swap) and a wavefront issues the
+// loads of a row batch no earlier than t0 + (stream rows it has issued so
+// far) * unit, where unit is the time the whole launch needs for one stream
+// row at the target rate.  A late wavefront never waits; every wait ends at its
+// deadline (the clock always advances) and is also capped by a poll count, so
+// the grid always drains.
+__device__ __forceinline__ unsigned long long pace_begin(const PaceArgs& p, int lane, bool first_thread) {
+    if (!p.unit_fp) return 0ull;
+    if (first_thread) p.slots[(p.seq + 32u) & 63u] = 0ull;  // recycle a slot for a later launch
+    const unsigned long long mine = __builtin_amdgcn_s_memrealtime();
+    unsigned long long seen = 0;
+    if (lane == 0) {
+        seen = atomicCAS(p.slots + (p.seq & 63u), 0ull, mine);
+        if (seen == 0ull) seen = mine;
+    }
+    // readfirstlane returns a signed int: go through unsigned before widening
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(seen >> 32));
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(seen & 0xffffffffull));
+    const unsigned long long t0v = ((unsigned long long)hi << 32) | (unsigned long long)lo;
+    return t0v;
+}
+__device__ __forceinline__ void pace_wait(const PaceArgs& p, unsigned long long t0, uint32_t units_done) {
+    if (!p.unit_fp) return;
+    const unsigned long long deadline = t0 + (((unsigned long long)units_done * p.unit_fp) >> 8);
+    for (int guard = 0; guard < (1 << 14); ++guard) {
+        if (__builtin_amdgcn_s_memrealtime() >= deadline) break;
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+
 template <typename T, int MODE, bool MOM, int U>
 __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
@@ -101,27 +146,35 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     const int wpb = waves / a.tpb;  // walkers per workgroup
     const int tile_l = wave / wpb;
     const int walk_l = wave - tile_l * wpb;
-    const int walker = blockIdx.y * wpb + walk_l;
-    const bool walker_on = walker < a.C * a.Q;
-
-    const int cyc = walker / a.Q;
-    const int seg = walker - cyc * a.Q;
-    const int p0 = (int)(((int64_t)seg * a.L) / a.Q);
-    const int p1 = (int)(((int64_t)(seg + 1) * a.L) / a.Q);
-    const int len = p1 - p0;
     const int n = a.ge.n;
     const int S = a.S;
-    const int row_first = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
     const int64_t ldT = a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
     const float third = 1.0f / 3.0f;
+    constexpr uint32_t kRowUnits = MOM ? 5u : 3u;  // 4-byte streams touched per row
 
-    // Grid-stride over column-tile groups.  With a grid sized to the resident
-    // workgroups of the chip (persistent launch) all wavefronts start row 0 of
-    // their tile together and stay in step, so at any moment the whole chip
-    // streams a few rows of x, m, g over a wide contiguous column window
-    // instead of touching all n rows of every array at once.
-    for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
+    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    uint32_t units_done = 0;
+
+    // Grid-stride over work items (walker group, tile group), tile group
+    // fastest.  With a grid sized to the resident workgroups of the chip
+    // (persistent launch) all wavefronts start the same rows together and,
+    // paced, stay in step: at any moment the whole chip streams a few rows of
+    // x, m, g over a wide contiguous column window instead of touching all n
+    // rows of every array at once.
+    const int64_t work = a.gx * a.gy;
+    for (int64_t w = blockIdx.x; w < work; w += gridDim.x) {
+        const int by = (int)(w / a.gx);
+        const int64_t bx = w - (int64_t)by * a.gx;
+        const int walker = by * wpb + walk_l;
+        const bool walker_on = walker < a.C * a.Q;
+        const int cyc = walker / a.Q;
+        const int seg = walker - cyc * a.Q;
+        const int p0 = (int)(((int64_t)seg * a.L) / a.Q);
+        const int p1 = (int)(((int64_t)(seg + 1) * a.L) / a.Q);
+        const int len = p1 - p0;
+        const int row_first = (int)(((int64_t)cyc + (int64_t)p0 * S) % n);
+
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
         const int64_t col = tile * kWave + lane;
         const bool on = walker_on && (col < a.ge.ncols);
@@ -168,6 +221,8 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             int rw[U];
         };
         auto load_full = [&](Batch& b) {
+            pace_wait(a.pace, t0, units_done);
+            units_done += U * kRowUnits;
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(b.xv[u], b.mv[u], b.gv[u], b.rw[u]);
         };
@@ -181,6 +236,8 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             {
                 T x0, m0, g0, x1, m1, g1;
                 int r0 = 0, r1 = 0;
+                pace_wait(a.pace, t0, units_done);
+                units_done += (len >= 2 ? 2u : 1u) * kRowUnits;
                 load_row(x0, m0, g0, r0);
                 if (len >= 2) load_row(x1, m1, g1, r1);
                 yf = y_of(x0, m0, g0, r0);
@@ -231,6 +288,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             for (int t = 0; t < tail; ++t) {
                 T xv, mv, gv;
                 int rw;
+                units_done += kRowUnits;
                 load_row(xv, mv, gv, rw);
                 emit(y_of(xv, mv, gv, rw), rw);
             }
@@ -272,6 +330,7 @@ struct GlobalArgs {
     int32_t xcd;
     int64_t gx;
     float inv_n;
+    PaceArgs pace;
 };
 
 template <typename T, bool MOM, int U>
@@ -293,6 +352,9 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     const int r0 = wrow * a.RL + lane_r;  // this lane's first row
     const int64_t ldT = a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
+    constexpr uint32_t kReadUnits = MOM ? 4u : 2u;  // 4-byte streams per row in the read phase
+    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    uint32_t units_done = 0;
 
     for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
@@ -309,6 +371,8 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         if (on) {
             for (int base = r0; base < n; base += RS * U) {
                 T xv[U], mv[U], gv[U];
+                pace_wait(a.pace, t0, units_done);
+                units_done += U * kReadUnits;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int row = base + u * RS;
@@ -353,6 +417,8 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         const T mean = sum * a.inv_n;
         if (on) {
             for (int base = r0; base < n; base += RS * U) {
+                pace_wait(a.pace, t0, units_done);
+                units_done += U;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int row = base + u * RS;
@@ -382,50 +448,108 @@ int pow2_ceil(int v) {
     return p;
 }
 
+// Launch plan shared by both kernels: `work` work items; persistent launches
+// use at most blocks_per_cu resident workgroups per compute unit (never more
+// than the kernel's occupancy allows, so that every workgroup is resident and
+// the paced wavefronts really run side by side).
+struct LaunchPlan {
+    int64_t work = 0;        // work items of a one-shot launch
+    int bpc = 0;             // requested resident workgroups per CU (0 = one-shot launch)
+    int num_cus = 0;
+    int waves = 0;           // wavefronts per workgroup
+    double pace_gbs = 0.0;   // target rate of a paced launch (0 = free running)
+    double clock_hz = 1e8;
+    int vec = 4;
+    const gpga_ctx* ctx = nullptr;
+};
+
+template <typename Args, typename Kernel>
+hipError_t launch_planned(Kernel kernel, LaunchPlan plan, Args a, hipStream_t st) {
+    const int threads = kWave * plan.waves;
+    int64_t blocks = plan.work;
+    a.pace.unit_fp = 0;
+    a.pace.slots = nullptr;
+    a.pace.seq = 0;
+    if (plan.bpc > 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, threads, 0) != hipSuccess || occ < 1) occ = 1;
+        const int bpc = plan.bpc < occ ? plan.bpc : occ;
+        const int64_t resident = (int64_t)plan.num_cus * bpc;
+        if (resident < blocks) blocks = resident;  // persistent: each workgroup strides over the work items
+        // Pacing needs every workgroup of the launch to be resident at once, which
+        // holds here: blocks <= CUs x workgroups per CU that fit.
+        gpga_ctx* c = const_cast<gpga_ctx*>(plan.ctx);
+        if (plan.pace_gbs > 0.0 && c->pace_slots) {
+            // time (clock counts x 256) for the whole launch to move one 4-byte stream row
+            const double bytes = (double)blocks * plan.waves * kWave * plan.vec * 4.0;
+            const double fp = bytes / (plan.pace_gbs * 1e9) * plan.clock_hz * 256.0;
+            if (fp >= 1.0 && fp < 4.0e9) {
+                a.pace.unit_fp = (uint32_t)fp;
+                a.pace.slots = c->pace_slots;
+                a.pace.seq = c->pace_seq++;
+            }
+        }
+    }
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(threads), 0, st, a);
+    return hipGetLastError();
+}
+
 template <typename T, int MODE, bool MOM>
-hipError_t launch_walk_u(int U, dim3 grid, dim3 block, hipStream_t st, const WalkArgs& a) {
+hipError_t launch_walk_u(int U, const LaunchPlan& plan, hipStream_t st, const WalkArgs& a) {
     switch (U) {
-        case 1: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 1>), grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 2>), grid, block, 0, st, a); break;
-        case 8: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 8>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((k_step_walk<T, MODE, MOM, 4>), grid, block, 0, st, a); break;
+        case 1: return launch_planned(k_step_walk<T, MODE, MOM, 1>, plan, a, st);
+        case 2: return launch_planned(k_step_walk<T, MODE, MOM, 2>, plan, a, st);
+        case 8: return launch_planned(k_step_walk<T, MODE, MOM, 8>, plan, a, st);
+        default: return launch_planned(k_step_walk<T, MODE, MOM, 4>, plan, a, st);
     }
-    return hipGetLastError();
 }
 
 template <typename T, bool MOM>
-hipError_t launch_walk_mode(int mode, int U, dim3 grid, dim3 block, hipStream_t st,
-                            const WalkArgs& a) {
+hipError_t launch_walk_mode(int mode, int U, const LaunchPlan& plan, hipStream_t st, const WalkArgs& a) {
     switch (mode) {
-        case MODE_RING: return launch_walk_u<T, MODE_RING, MOM>(U, grid, block, st, a);
-        case MODE_PEER: return launch_walk_u<T, MODE_PEER, MOM>(U, grid, block, st, a);
-        default: return launch_walk_u<T, MODE_SELF, MOM>(U, grid, block, st, a);
+        case MODE_RING: return launch_walk_u<T, MODE_RING, MOM>(U, plan, st, a);
+        case MODE_PEER: return launch_walk_u<T, MODE_PEER, MOM>(U, plan, st, a);
+        default: return launch_walk_u<T, MODE_SELF, MOM>(U, plan, st, a);
     }
 }
 
 template <typename T, bool MOM>
-hipError_t launch_global_u(int U, dim3 grid, dim3 block, hipStream_t st, const GlobalArgs& a) {
+hipError_t launch_global_u(int U, const LaunchPlan& plan, hipStream_t st, const GlobalArgs& a) {
     switch (U) {
-        case 1: hipLaunchKernelGGL((k_step_global<T, MOM, 1>), grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((k_step_global<T, MOM, 2>), grid, block, 0, st, a); break;
-        case 8: hipLaunchKernelGGL((k_step_global<T, MOM, 8>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((k_step_global<T, MOM, 4>), grid, block, 0, st, a); break;
+        case 1: return launch_planned(k_step_global<T, MOM, 1>, plan, a, st);
+        case 2: return launch_planned(k_step_global<T, MOM, 2>, plan, a, st);
+        case 8: return launch_planned(k_step_global<T, MOM, 8>, plan, a, st);
+        default: return launch_planned(k_step_global<T, MOM, 4>, plan, a, st);
     }
-    return hipGetLastError();
 }
 
-// Waves in flight that saturate the chip: 256 CUs x 4 SIMDs x a few waves each.
-constexpr int64_t kEnoughWaves = 16384;
+// From this many whole-column walkers on (half of the 256 CUs x 16 resident
+// wavefronts) the chip is kept busy with one wavefront per column tile walking
+// all its rows, which is the shape the paced launch needs; below it the rows
+// are split over lanes / wavefronts of a workgroup instead.
+constexpr int64_t kPacedWaves = 2048;
 
-// Workgroups launched along x.  Persistent launch: as many as are resident at
-// once (CUs x workgroups per CU), each striding over the tile groups, which
-// keeps all wavefronts on the same few rows at the same time.
-int64_t persistent_grid_x(const gpga_ctx* c, int64_t gx, int64_t gy) {
-    const int bpc = c->opt_blocks_per_cu < 0 ? kDefaultBlocksPerCu : c->opt_blocks_per_cu;
-    if (bpc == 0) return gx;
-    int64_t resident = ((int64_t)c->num_cus * bpc) / (gy > 0 ? gy : 1);
-    if (resident < 1) resident = 1;
-    return gx < resident ? gx : resident;
+// Default policy: large launches whose wavefronts each walk many rows run
+// persistent and paced; everything else is a one-shot launch.
+constexpr int kAutoBlocksPerCu = 4;
+constexpr double kAutoPaceGbsWalk = 6200.0;    // measured optimum of the gossip walk (cfg3 shape)
+constexpr double kAutoPaceGbsGlobal = 5700.0;  // the global-average kernel saturates a little lower
+constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
+
+LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool walks_rows, double auto_gbs) {
+    LaunchPlan p;
+    p.work = work;
+    p.num_cus = c->num_cus;
+    p.waves = waves;
+    p.vec = vec;
+    p.ctx = c;
+    p.clock_hz = c->clock_hz;
+    const bool big = walks_rows && vec == 4 && (int64_t)c->n * c->d * 4 >= kPaceMinBytes;
+    p.bpc = c->opt_blocks_per_cu < 0 ? (big ? kAutoBlocksPerCu : 0) : c->opt_blocks_per_cu;
+    p.pace_gbs = c->opt_pace_gbs < 0 ? (big ? auto_gbs : 0.0) : (double)c->opt_pace_gbs;
+    if (!walks_rows) p.pace_gbs = 0.0;
+    return p;
 }
 
 }  // namespace
@@ -452,7 +576,9 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     if (mode != MODE_SELF) {
         if (c->opt_row_split) {
             Q = c->opt_row_split;
-        } else if (tiles * a.C < kEnoughWaves) {
+        } else if (tiles * a.C < kPacedWaves) {
+            // too few column tiles to occupy the chip with one walker per cycle:
+            // split each cycle over the wavefronts of a workgroup (LDS exchange)
             Q = pow2_floor(a.L / 4 > 0 ? a.L / 4 : 1);  // keep segments of >= 4 rows
         }
         if (Q > waves) Q = waves;
@@ -465,18 +591,21 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     a.tpb = waves / wpb;
     const int64_t gx = (tiles + a.tpb - 1) / a.tpb;
     const int64_t gy = ((int64_t)a.C * Q + wpb - 1) / wpb;
-    if (gx > 0x7fffffffLL || gy > 65535) return hipErrorInvalidConfiguration;
+    if (gx * gy > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.gx = gx;
+    a.gy = gy;
     a.xcd = c->opt_xcd_swizzle;
-    const int64_t launch_x = persistent_grid_x(c, gx, gy);
-    dim3 grid((unsigned)launch_x, (unsigned)gy), block(kWave * waves);
+    // pacing assumes every wavefront does the same work: one walker per cycle, equal segments
+    const bool uniform = (Q == 1) && (((int64_t)a.C * Q) % wpb == 0);
+    // short cycles (< 8 rows per wavefront) already keep few rows open in a one-shot launch
+    const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= 8, kAutoPaceGbsWalk);
     const bool mom = c->mu != 0.f;
     if (vec == 4) {
-        return mom ? launch_walk_mode<v4f, true>(mode, U, grid, block, c->stream, a)
-                   : launch_walk_mode<v4f, false>(mode, U, grid, block, c->stream, a);
+        return mom ? launch_walk_mode<v4f, true>(mode, U, plan, c->stream, a)
+                   : launch_walk_mode<v4f, false>(mode, U, plan, c->stream, a);
     }
-    return mom ? launch_walk_mode<float, true>(mode, U, grid, block, c->stream, a)
-               : launch_walk_mode<float, false>(mode, U, grid, block, c->stream, a);
+    return mom ? launch_walk_mode<float, true>(mode, U, plan, c->stream, a)
+               : launch_walk_mode<float, false>(mode, U, plan, c->stream, a);
 }
 
 hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
@@ -493,13 +622,13 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     int RL = 1, wpb = 1;
     if (c->opt_row_lanes) {
         RL = c->opt_row_lanes;
-    } else if (tiles64 < kEnoughWaves / 8) {
+    } else if (tiles64 < kPacedWaves) {
         RL = 4;
     }
     while (RL > 1 && RL > n) RL >>= 1;
     if (c->opt_row_split) {
         wpb = c->opt_row_split;
-    } else if (tiles64 * RL < kEnoughWaves) {
+    } else if (tiles64 < kPacedWaves) {
         wpb = pow2_floor(n / (4 * RL) > 0 ? n / (4 * RL) : 1);
     }
     if (wpb > waves) wpb = waves;
@@ -512,13 +641,12 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     if (gx > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.gx = gx;
     a.xcd = c->opt_xcd_swizzle;
-    const int64_t launch_x = persistent_grid_x(c, gx, 1);
-    dim3 grid((unsigned)launch_x), block(kWave * waves);
+    const LaunchPlan plan = make_plan(c, gx, waves, vec, RL == 1 && wpb == 1 && n >= 8, kAutoPaceGbsGlobal);
     const bool mom = c->mu != 0.f;
     if (vec == 4) {
-        return mom ? launch_global_u<v4f, true>(U, grid, block, c->stream, a)
-                   : launch_global_u<v4f, false>(U, grid, block, c->stream, a);
+        return mom ? launch_global_u<v4f, true>(U, plan, c->stream, a)
+                   : launch_global_u<v4f, false>(U, plan, c->stream, a);
     }
-    return mom ? launch_global_u<float, true>(U, grid, block, c->stream, a)
-               : launch_global_u<float, false>(U, grid, block, c->stream, a);
+    return mom ? launch_global_u<float, true>(U, plan, c->stream, a)
+               : launch_global_u<float, false>(U, plan, c->stream, a);
 }

@@ -129,6 +129,32 @@ def test_every_launch_geometry_gives_the_same_answer(hx, opts, n, d, topology):
         sim.close()
 
 
+@pytest.mark.parametrize("topology,k,H", [("ring", 0, 0), ("expo1", 0, 0), ("expo1", 3, 0), ("expo1", 5, 0),
+                                          ("ring", 5, 6), ("none", 1, 0)])
+@pytest.mark.parametrize("opts", [{"blocks_per_cu": 1, "waves": 1, "pace_gbs": 2000},
+                                  {"blocks_per_cu": 2, "waves": 2, "pace_gbs": 8000, "unroll": 4},
+                                  {"blocks_per_cu": 1, "waves": 4, "pace_gbs": 0, "unroll": 1}],
+                         ids=["paced-w1", "paced-w2-u4", "persistent-unpaced"])
+def test_persistent_paced_launch_matches_oracle(hx, topology, k, H, opts):
+    # wide enough that the work items exceed the resident workgroups: the grid-stride
+    # loop, the shared start time and the deadline waits are all exercised
+    n, d = 64, 300_004
+    X, Mb, G = inputs.random_state(n, d, seed=99)
+    sim = hx.Simulation(n, d, topology=topology, H=H, lr=0.1, momentum=0.9)
+    for name, v in opts.items():
+        sim.set_option(name, v)
+    X_ref, M_ref = X, Mb
+    sim.set_state(X=X, M=Mb, G=G, k=k)
+    for j in range(3):          # several launches in a row reuse / recycle the start-time slots
+        sim.step()
+        X_ref, M_ref = orc.gossip_pga_step(X_ref, M_ref, G, k + j, topology=topology, H=H, lr=0.1, momentum=0.9)
+        X_ref = X_ref.astype(np.float32).astype(np.float64)
+        M_ref = M_ref.astype(np.float32).astype(np.float64)
+        assert_close(host(sim.X), X_ref, TOL_STEP, f"X after step {j}")
+        assert_close(host(sim.M), M_ref, TOL_STEP, f"M after step {j}")
+    sim.close()
+
+
 def test_padding_columns_and_inputs_are_untouched(hx):
     n, d, ld = 8, 1001, 1008
     sim = hx.Simulation(n, d, topology="ring", H=0, lr=0.1, momentum=0.9, ld=ld)
