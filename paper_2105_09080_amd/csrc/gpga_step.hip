@@ -533,7 +533,7 @@ constexpr int64_t kPacedWaves = 2048;
 // Default policy: large launches whose wavefronts each walk many rows run
 // persistent and paced; everything else is a one-shot launch.
 constexpr int kAutoBlocksPerCu = 4;
-constexpr double kAutoPaceGbsWalk = 6200.0;    // measured optimum of the gossip walk (cfg3 shape)
+constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
 constexpr double kAutoPaceGbsGlobal = 5700.0;  // the global-average kernel saturates a little lower
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
@@ -569,7 +569,6 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
         a.L = n / a.C;
     }
     const int waves = c->opt_waves ? c->opt_waves : 4;
-    const int U = c->opt_unroll ? c->opt_unroll : kDefaultUnroll;
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
 
     int Q = 1;
@@ -585,8 +584,13 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
         if (Q > a.L) Q = pow2_floor(a.L);
     }
     a.Q = Q;
+    // Walkers per workgroup.  One walker per cycle and plenty of tiles: give a
+    // workgroup adjacent tiles of ONE cycle (wpb = 1), so that a launch works on
+    // one cycle group at a time and few rows are open at once.  Otherwise pack
+    // the walkers of a tile into one workgroup.
     int wpb = pow2_ceil((int)((int64_t)a.C * Q > waves ? waves : a.C * Q));
     if (wpb > waves) wpb = waves;
+    if (Q == 1 && tiles >= kPacedWaves && !c->opt_row_split) wpb = 1;
     if (wpb < Q) wpb = Q;
     a.tpb = waves / wpb;
     const int64_t gx = (tiles + a.tpb - 1) / a.tpb;
@@ -599,6 +603,8 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const bool uniform = (Q == 1) && (((int64_t)a.C * Q) % wpb == 0);
     // short cycles (< 8 rows per wavefront) already keep few rows open in a one-shot launch
     const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= 8, kAutoPaceGbsWalk);
+    // paced wavefronts advance one row per batch (two rows in flight); free-running ones two
+    const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : kDefaultUnroll);
     const bool mom = c->mu != 0.f;
     if (vec == 4) {
         return mom ? launch_walk_mode<v4f, true>(mode, U, plan, c->stream, a)
