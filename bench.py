@@ -32,8 +32,8 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 # (FETCH_SIZE run + WRITE_SIZE run, scaled by a copy kernel of known size); the
 # summaries live under profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3/ring": 32768038263,   # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
-    "cfg4/expo1": 140800205238,  # profiles/step_cfg4_expo1.md
+    "cfg3/ring": 32768495263,   # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
+    "cfg4/expo1": 140812175038,  # profiles/step_cfg4_expo1.md
 }
 
 
