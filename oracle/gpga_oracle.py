@@ -27,6 +27,11 @@ What each function follows (Gossip-PGA paper, arXiv 2105.09080):
   m <- mu m + g, x^{k+1/2} = x - gamma m.  mu = 0 is Algorithm 1 exactly.  The
   momentum buffer is node-local and never mixed (only model parameters are
   communicated, App. F.1).
+* ``GossipAGA``        - Algorithm 2 (App. G), the adaptive averaging period:
+  a counter C of iterations since the last global average; when C reaches the
+  current H the step is a global average, the minibatch losses are averaged
+  over nodes, and either the warm-up estimate F_init <- (F_init + F)/2 is
+  refreshed (k < K_w) or H <- ceil(F_init / F * H_init).
 * counter RNG          - Philox4x32-10 (Salmon et al., SC'11) + Box-Muller,
   the generator specification shared *as a specification* with the HIP path
   (each side has its own implementation).
@@ -353,3 +358,64 @@ class GossipPGA:
         self.X, self.M = self._store(X_next), self._store(M_next)
         self.k += 1
         return self.X
+
+
+class GossipAGA:
+    """Gossip-AGA, Algorithm 2: Gossip-PGA whose period H adapts to the loss.
+
+    Per iteration k (0-based): C <- C+1; gradients and minibatch losses F_i at the
+    current rows; local (momentum) update; if C == H: C <- 0, global average,
+    F = (1/n) sum_i F_i, then F_init <- (F_init + F)/2 while k < K_w, else
+    H <- ceil(F_init / F * H_init); otherwise one gossip step with W_k.
+    F_init starts at 0 as printed.  Readings where the listing is silent: the
+    one-peer offset is driven by the iteration counter k; H is kept in
+    [1, H_max] (the analysis needs a finite H_max, Corollary 1; H >= 1 keeps
+    the counter test meaningful if F_init is still 0 or F is 0).
+    """
+
+    def __init__(self, n: int, d: int, *, topology: str, H_init: int, warmup_iters: int,
+                 H_max: int, lr: float, momentum: float = 0.0, x0=None, storage: str = "f32"):
+        self.pga = GossipPGA(n, d, topology=topology, H=0, lr=lr, momentum=momentum, x0=x0,
+                             storage=storage)
+        self.H_init, self.K_w, self.H_max = int(H_init), int(warmup_iters), int(H_max)
+        self.H = int(H_init)
+        self.C = 0
+        self.F_init = 0.0
+        self.history = []        # (k, H after the update) at every global average
+
+    @property
+    def X(self):
+        return self.pga.X
+
+    @property
+    def M(self):
+        return self.pga.M
+
+    @property
+    def k(self):
+        return self.pga.k
+
+    def step(self, G, losses):
+        """Consume gradients G (n,d) and minibatch losses (n,) of iteration k."""
+        p = self.pga
+        k = p.k
+        self.C += 1
+        G = p._store(G)
+        Y, M_next = local_update(p.X, p.M, G, p.lr, p.momentum)
+        if self.C == self.H:
+            self.C = 0
+            xbar = Y.mean(axis=0)
+            X_next = np.broadcast_to(xbar, Y.shape).copy()
+            F = float(np.mean(np.asarray(p._store(losses), dtype=np.float64)))
+            if k < self.K_w:
+                self.F_init = 0.5 * (self.F_init + F)
+            else:
+                ratio = self.F_init / F if F > 0.0 else float("inf")
+                H_new = math.ceil(ratio * self.H_init) if math.isfinite(ratio) else self.H_max
+                self.H = int(min(max(H_new, 1), self.H_max))
+            self.history.append((k, self.H))
+        else:
+            X_next = mixing_matrix(p.topology, p.n, k) @ Y
+        p.X, p.M = p._store(X_next), p._store(M_next)
+        p.k += 1
+        return p.X

@@ -442,3 +442,62 @@ def test_fp32_storage_mode_rounds_state_only_between_steps():
         assert np.array_equal(a.M, a.M.astype(np.float32).astype(np.float64))
     np.testing.assert_allclose(a.X, b.X, rtol=0, atol=1e-5)
     assert not np.array_equal(a.X, b.X)
+
+
+# ---------------------------------------------------------------- adaptive period (Algorithm 2)
+
+def test_aga_period_schedule_on_a_hand_worked_example():
+    # H_init = 2, K_w = 4, losses identical on all nodes: F_k = 8 / (k + 1).
+    # k=1: C hits 2 -> average; k < 4: F_init = (0 + 4)/2 = 2
+    # k=3: average; k < 4: F_init = (2 + 2)/2 = 2
+    # k=5: average; F = 8/6:   H = ceil(2 / (8/6) * 2)  = ceil(3)   = 3
+    # k=8: average; F = 8/9:   H = ceil(2 / (8/9) * 2)  = ceil(4.5) = 5
+    # k=13: average; F = 8/14: H = ceil(2 / (8/14) * 2) = ceil(7)   = 7
+    # k=20: average; F = 8/21: H = ceil(10.5) = 11 -> capped at H_max = 9
+    n, d = 4, 3
+    sim = orc.GossipAGA(n, d, topology="ring", H_init=2, warmup_iters=4, H_max=9, lr=0.1, storage="f64")
+    averaged_at = []
+    for k in range(24):
+        G = RNG.standard_normal((n, d))
+        sim.step(G, np.full(n, 8.0 / (k + 1)))
+        rows_equal = all(np.array_equal(sim.X[0], sim.X[i]) for i in range(n))
+        if rows_equal:
+            averaged_at.append(k)
+    assert averaged_at == [1, 3, 5, 8, 13, 20]
+    assert sim.history == [(1, 2), (3, 2), (5, 3), (8, 5), (13, 7), (20, 9)]
+    assert sim.F_init == 2.0
+
+
+def test_aga_with_constant_period_is_gossip_pga():
+    # losses chosen so that ceil(F_init / F * H_init) stays H_init: the counter schedule
+    # then averages exactly when mod(k+1, H) = 0, i.e. Algorithm 1
+    n, d, H = 6, 4, 3
+    aga = orc.GossipAGA(n, d, topology="expo1", H_init=H, warmup_iters=7, H_max=50, lr=0.05, momentum=0.9,
+                        storage="f64")
+    pga = orc.GossipPGA(n, d, topology="expo1", H=H, lr=0.05, momentum=0.9, storage="f64")
+    for k in range(20):
+        G = RNG.standard_normal((n, d))
+        # warm-up (k = 2, 5 < 7) sees F = 4, 4: F_init = 2, then 3; afterwards F = 3.2 gives
+        # ceil(3 / 3.2 * 3) = ceil(2.8125) = 3
+        aga.step(G, np.full(n, 4.0 if k < 7 else 3.2))
+        pga.step(G)
+        np.testing.assert_allclose(aga.X, pga.X, atol=1e-15)
+        np.testing.assert_allclose(aga.M, pga.M, atol=1e-15)
+    assert aga.F_init == 3.0 and aga.H == H
+
+
+def test_aga_uses_the_node_mean_of_the_losses_and_clamps_the_period():
+    n, d = 5, 2
+    sim = orc.GossipAGA(n, d, topology="ring", H_init=2, warmup_iters=2, H_max=6, lr=0.1, storage="f64")
+    Z = np.zeros((n, d))
+    sim.step(Z, np.arange(n, dtype=float))            # k=0: C=1
+    sim.step(Z, np.array([1.0, 2.0, 3.0, 4.0, 10.0]))  # k=1: average, warm-up: F = 4 -> F_init = 2
+    assert sim.F_init == 2.0
+    sim.step(Z, np.ones(n))
+    sim.step(Z, np.array([0.5, 0.5, 0.5, 0.5, 0.5]))   # k=3: F = 0.5 -> ceil(2/0.5*2) = 8 -> clamp 6
+    assert sim.H == 6
+    for _ in range(6):
+        sim.step(Z, np.full(n, 100.0))                 # next average at k=9: ceil(2/100*2) = 1
+    assert sim.H == 1 and sim.history[-1] == (9, 1)
+    sim.step(Z, np.zeros(n))                           # F = 0: period goes to H_max
+    assert sim.H == 6
