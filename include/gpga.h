@@ -138,6 +138,21 @@ gpga_status gpga_local_loss(gpga_ctx* ctx, const int32_t* batch_idx_dev, int32_t
  * m and x_new once; then swaps x / x_new and increments k. */
 gpga_status gpga_step(gpga_ctx* ctx);
 
+/* Adaptive averaging period, Gossip-AGA (Algorithm 2, App. G).  After
+ * gpga_aga_enable the period starts at H_init and iterations are advanced with
+ * gpga_aga_step instead of gpga_step: a counter C of iterations since the last
+ * global average is incremented; when C reaches the current H the step is a
+ * global average, F = (1/n) sum_i loss_dev[i] is formed, and either the warm-up
+ * estimate F_init <- (F_init + F)/2 is refreshed (iteration k < warmup_iters;
+ * F_init starts at 0) or H <- ceil(F_init / F * H_init), kept in [1, H_max].
+ * loss_dev: n floats on the device, the minibatch losses F_i(x_i^(k); xi_i) of
+ * this iteration (gpga_local_loss, called before the step).  Averaging steps
+ * synchronise the stream (one scalar is read back).  1 <= H_init <= H_max. */
+gpga_status gpga_aga_enable(gpga_ctx* ctx, int64_t H_init, int64_t warmup_iters, int64_t H_max);
+gpga_status gpga_aga_step(gpga_ctx* ctx, const float* loss_dev);
+/* Current averaging period H. */
+int64_t gpga_period(const gpga_ctx* ctx);
+
 /* Consensus distance ||X^(k) - 1 xbar^T||_F (Sec. 4; App. B) of the live X.
  * Synchronises the stream; *out_host is a host double. */
 gpga_status gpga_consensus_error(gpga_ctx* ctx, double* out_host);

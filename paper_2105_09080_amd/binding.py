@@ -41,6 +41,9 @@ SIGNATURES = [
     ("gpga_local_grad", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int32]),
     ("gpga_local_loss", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int32, _c.c_void_p]),
     ("gpga_step", _c.c_int, [_ctx_p]),
+    ("gpga_aga_enable", _c.c_int, [_ctx_p, _c.c_int64, _c.c_int64, _c.c_int64]),
+    ("gpga_aga_step", _c.c_int, [_ctx_p, _c.c_void_p]),
+    ("gpga_period", _c.c_int64, [_ctx_p]),
     ("gpga_consensus_error", _c.c_int, [_ctx_p, _c.POINTER(_c.c_double)]),
     ("gpga_mean", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_current_x", _c.c_int, [_ctx_p, _c.POINTER(_c.c_void_p)]),
@@ -155,6 +158,18 @@ def gpga_local_loss(ctx, batch_idx, B: int, loss):
 
 def gpga_step(ctx):
     _check(ctx, _lib.gpga_step(ctx))
+
+
+def gpga_aga_enable(ctx, H_init: int, warmup_iters: int, H_max: int):
+    _check(ctx, _lib.gpga_aga_enable(ctx, H_init, warmup_iters, H_max))
+
+
+def gpga_aga_step(ctx, loss):
+    _check(ctx, _lib.gpga_aga_step(ctx, _ptr(loss)))
+
+
+def gpga_period(ctx) -> int:
+    return int(_lib.gpga_period(ctx))
 
 
 def gpga_consensus_error(ctx) -> float:

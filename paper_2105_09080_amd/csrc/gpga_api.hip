@@ -316,12 +316,8 @@ gpga_status gpga_local_loss(gpga_ctx* c, const int32_t* batch_idx, int32_t B, fl
     return run_grad(c, batch_idx, B, loss_dev);
 }
 
-gpga_status gpga_step(gpga_ctx* c) {
-    if (!c) return GPGA_EINVAL;
-    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
-    DeviceGuard guard(c->device);
-
-    const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
+// One fused iteration; `global` selects the all-node mean instead of the gossip mix.
+static gpga_status run_step(gpga_ctx* c, bool global) {
     int mode = MODE_SELF;
     int32_t S = 0;
     if (!global && c->n > 1) {
@@ -362,6 +358,64 @@ gpga_status gpga_step(gpga_ctx* c) {
     c->k += 1;
     return GPGA_OK;
 }
+
+gpga_status gpga_step(gpga_ctx* c) {
+    if (!c) return GPGA_EINVAL;
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    if (c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is enabled: call gpga_aga_step");
+    DeviceGuard guard(c->device);
+    const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
+    return run_step(c, global);
+}
+
+gpga_status gpga_aga_enable(gpga_ctx* c, int64_t H_init, int64_t warmup_iters, int64_t H_max) {
+    if (!c) return GPGA_EINVAL;
+    if (H_init < 1 || H_max < H_init || warmup_iters < 0)
+        return fail(c, GPGA_EINVAL, "need 1 <= H_init <= H_max and warmup_iters >= 0");
+    c->aga = true;
+    c->aga_H_init = H_init;
+    c->aga_warmup = warmup_iters;
+    c->aga_H_max = H_max;
+    c->aga_C = 0;
+    c->aga_F_init = 0.0;
+    c->H = H_init;
+    return GPGA_OK;
+}
+
+gpga_status gpga_aga_step(gpga_ctx* c, const float* loss_dev) {
+    if (!c) return GPGA_EINVAL;
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    if (!c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is not enabled (gpga_aga_enable)");
+    if (!loss_dev || !aligned(loss_dev, 4)) return fail(c, GPGA_EINVAL, "loss_dev must be a 4-byte aligned device pointer");
+    DeviceGuard guard(c->device);
+    const int64_t k = c->k;
+    c->aga_C += 1;
+    const bool global = (c->aga_C == c->H);
+    gpga_status s = run_step(c, global);
+    if (s != GPGA_OK || !global) return s;
+    c->aga_C = 0;
+    // F = (1/n) sum_i F_i of this iteration's minibatches: one scalar back to the host
+    hipError_t e = launch_mean_f32(c, loss_dev, c->n, c->partials);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(c->host_scalar, c->partials, sizeof(double), hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return hip_fail(c, e, "loss average");
+    const double F = *c->host_scalar;
+    if (k < c->aga_warmup) {
+        c->aga_F_init = 0.5 * (c->aga_F_init + F);
+    } else {
+        int64_t H_new = c->aga_H_max;
+        if (F > 0.0) {
+            const double h = std::ceil(c->aga_F_init / F * (double)c->aga_H_init);
+            if (std::isfinite(h) && h < (double)c->aga_H_max) H_new = (int64_t)h;
+        }
+        if (H_new < 1) H_new = 1;
+        c->H = H_new;
+    }
+    return GPGA_OK;
+}
+
+int64_t gpga_period(const gpga_ctx* c) { return c ? c->H : -1; }
 
 gpga_status gpga_consensus_error(gpga_ctx* c, double* out_host) {
     if (!c) return GPGA_EINVAL;

@@ -68,6 +68,11 @@ struct gpga_ctx {
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
     unsigned long long* pace_slots = nullptr;  // 64 device words, library-owned
 
+    // adaptive averaging period (Algorithm 2)
+    bool aga = false;
+    int64_t aga_H_init = 0, aga_warmup = 0, aga_H_max = 0, aga_C = 0;
+    double aga_F_init = 0.0;
+
     char err[256] = {0};
 };
 
@@ -102,3 +107,5 @@ hipError_t launch_col_mean(const gpga_ctx* c, float* xbar);
 // Sum of squared deviations into c->partials[0] (device double).
 hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed);
 size_t consensus_partials_needed(const gpga_ctx* c);
+// out[0] = mean of count floats (one workgroup, fp64 accumulation).
+hipError_t launch_mean_f32(const gpga_ctx* c, const float* v, int64_t count, double* out);

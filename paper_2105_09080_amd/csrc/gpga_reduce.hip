@@ -148,6 +148,19 @@ __global__ void __launch_bounds__(256) k_final_sum(const double* __restrict__ pa
     if (threadIdx.x == 0) out[0] = (s_buf[0] + s_buf[1]) + (s_buf[2] + s_buf[3]);
 }
 
+// out[0] = (1/count) sum v[i], one workgroup, fixed order.
+__global__ void __launch_bounds__(256) k_mean_f32(const float* __restrict__ v, int64_t count,
+                                                  double* __restrict__ out) {
+    __shared__ double s_buf[4];
+    double acc = 0.0;
+    for (int64_t t = threadIdx.x; t < count; t += blockDim.x) acc += (double)v[t];
+    acc = wave_sum(acc);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) s_buf[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = ((s_buf[0] + s_buf[1]) + (s_buf[2] + s_buf[3])) / (double)count;
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) k_fill_rows(float* __restrict__ dst, int64_t ld,
                                                    int64_t col0, int64_t ncols, int32_t n,
@@ -217,5 +230,10 @@ hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
                            c->ld, nv * 4, tail, c->n, parts + b1);
     }
     hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(256), 0, c->stream, parts, b1 + b2, c->partials);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean_f32(const gpga_ctx* c, const float* v, int64_t count, double* out) {
+    hipLaunchKernelGGL(k_mean_f32, dim3(1), dim3(256), 0, c->stream, v, count, out);
     return hipGetLastError();
 }

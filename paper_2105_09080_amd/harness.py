@@ -116,6 +116,16 @@ class Simulation:
     def step(self):
         B.gpga_step(self.ctx)
 
+    def aga_enable(self, H_init: int, warmup_iters: int, H_max: int):
+        B.gpga_aga_enable(self.ctx, H_init, warmup_iters, H_max)
+
+    def aga_step(self, loss: torch.Tensor):
+        B.gpga_aga_step(self.ctx, loss)
+
+    @property
+    def period(self) -> int:
+        return B.gpga_period(self.ctx)
+
     def consensus_error(self) -> float:
         return B.gpga_consensus_error(self.ctx)
 

@@ -532,3 +532,37 @@ def test_error_paths_return_status_codes(hx):
     with pytest.raises(B.GpgaError):
         B.gpga_set_option(ctx, "nonsense", 1)
     B.gpga_destroy(ctx)
+
+
+# ------------------------------------------------------------------ adaptive period (Algorithm 2)
+
+@pytest.mark.parametrize("topology", ["ring", "expo1"])
+def test_gossip_aga_trajectory_and_period_sequence(hx, topology):
+    n, d, M, B, T = 16, 512, 64, 8, 80
+    H_init, K_w, H_max, lr, mu = 2, 8, 12, 0.5, 0.9
+    feat, y, _ = inputs.logreg_problem(n, d, M, seed=21)
+    feat = (feat / math.sqrt(d)).astype(np.float32)
+    idx = inputs.batch_indices(T, n, B, M, seed=21)
+    sim = hx.Simulation(n, d, topology=topology, H=0, lr=lr, momentum=mu)
+    sim.problem_logreg(feat, y)
+    sim.aga_enable(H_init, K_w, H_max)
+    idx_d = sim.upload_batches(idx)
+    ref = orc.GossipAGA(n, d, topology=topology, H_init=H_init, warmup_iters=K_w, H_max=H_max, lr=lr,
+                        momentum=mu, storage="f32")
+    periods = []
+    for k in range(T):
+        loss = sim.local_loss(idx_d[k])
+        sim.local_grad(idx_d[k])
+        sim.aga_step(loss)
+        ref.step(orc.logreg_grad(feat, y, ref.X, idx[k]), orc.logreg_loss(feat, y, ref.X, idx[k]))
+        periods.append(sim.period)
+        assert sim.period == ref.H, f"period differs at step {k}: {sim.period} vs {ref.H}"
+        if ref.history and ref.history[-1][0] == k:          # a global average just happened
+            Xg = sim.X.cpu().numpy()
+            assert all(np.array_equal(Xg[0], Xg[i]) for i in range(n))
+    assert_close(host(sim.X), ref.X, TOL_FINAL, "final iterate")
+    assert_close(host(sim.M), ref.M, TOL_FINAL, "final momentum")
+    assert len(set(periods)) > 1, "the period never adapted in this run"
+    with pytest.raises(Exception):
+        sim.step()                                            # plain step is refused while AGA is on
+    sim.close()
