@@ -368,7 +368,79 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + coff;
 
         T sum = T(0);
-        if (on) {
+        if (on && RS == 1) {
+            // One lane walks all n rows of its column group: same software pipeline
+            // as the gossip walk (next batch's loads are issued ahead of this
+            // batch's stores of m; branch-free hot loop).
+            struct Batch {
+                T xv[U], mv[U], gv[U];
+            };
+            int row = 0;
+            auto load_full = [&](Batch& b) {
+                pace_wait(a.pace, t0, units_done);
+                units_done += U * kReadUnits;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t off = (int64_t)(row + u) * ldT;
+                    b.xv[u] = ld_stream(xp + off);
+                    if (MOM) b.mv[u] = ld_stream(mp + off);
+                    b.gv[u] = ld_stream(gp + off);
+                }
+                row += U;
+            };
+            auto process_full = [&](const Batch& b, int first_row) {
+                T part = T(0);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    T mom = b.gv[u];
+                    if (MOM) {
+                        mom = mu * b.mv[u] + b.gv[u];
+                        st_stream(mp + (int64_t)(first_row + u) * ldT, mom);
+                    }
+                    part += b.xv[u] - lr * mom;
+                }
+                sum += part;
+            };
+            const int nfull = n / U;
+            Batch A, B;
+            int done = 0;
+            if (nfull >= 1) {
+                load_full(A);
+                int b = 0;
+                for (; b + 3 <= nfull; b += 2) {
+                    load_full(B);
+                    __builtin_amdgcn_sched_barrier(0);
+                    process_full(A, done);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_full(A);
+                    __builtin_amdgcn_sched_barrier(0);
+                    process_full(B, done + U);
+                    __builtin_amdgcn_sched_barrier(0);
+                    done += 2 * U;
+                }
+                if (nfull - b == 2) {
+                    load_full(B);
+                    __builtin_amdgcn_sched_barrier(0);
+                    process_full(A, done);
+                    process_full(B, done + U);
+                    done += 2 * U;
+                } else {
+                    process_full(A, done);
+                    done += U;
+                }
+            }
+            for (; done < n; ++done) {
+                const int64_t off = (int64_t)done * ldT;
+                const T xv = ld_stream(xp + off);
+                T mom = ld_stream(gp + off);
+                if (MOM) {
+                    mom = mu * ld_stream(mp + off) + mom;
+                    st_stream(mp + off, mom);
+                }
+                units_done += kReadUnits;
+                sum += xv - lr * mom;
+            }
+        } else if (on) {
             for (int base = r0; base < n; base += RS * U) {
                 T xv[U], mv[U], gv[U];
                 pace_wait(a.pace, t0, units_done);
@@ -534,7 +606,7 @@ constexpr int64_t kPacedWaves = 2048;
 // persistent and paced; everything else is a one-shot launch.
 constexpr int kAutoBlocksPerCu = 4;
 constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
-constexpr double kAutoPaceGbsGlobal = 5700.0;  // the global-average kernel saturates a little lower
+constexpr double kAutoPaceGbsGlobal = 5950.0;  // the global-average kernel saturates a little lower
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
 LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool walks_rows, double auto_gbs) {
@@ -621,7 +693,6 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     a.ge = ge;
     a.inv_n = 1.0f / (float)n;
     const int waves = c->opt_waves ? c->opt_waves : 4;
-    const int U = c->opt_unroll ? c->opt_unroll : 4;
 
     // Spread rows over lanes and waves only when columns alone cannot fill the chip.
     const int64_t tiles64 = (ge.ncols + kWave - 1) / kWave;
@@ -648,6 +719,7 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     a.gx = gx;
     a.xcd = c->opt_xcd_swizzle;
     const LaunchPlan plan = make_plan(c, gx, waves, vec, RL == 1 && wpb == 1 && n >= 8, kAutoPaceGbsGlobal);
+    const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : 4);
     const bool mom = c->mu != 0.f;
     if (vec == 4) {
         return mom ? launch_global_u<v4f, true>(U, plan, c->stream, a)
