@@ -27,6 +27,14 @@ What each function follows (Gossip-PGA paper, arXiv 2105.09080):
   m <- mu m + g, x^{k+1/2} = x - gamma m.  mu = 0 is Algorithm 1 exactly.  The
   momentum buffer is node-local and never mixed (only model parameters are
   communicated, App. F.1).
+* Nesterov momentum    - the image-classification runs use "Nesterov momentum
+  SGD" (App. F.1) from the deep-learning framework the paper names; its form is
+  m <- mu m + g, x^{k+1/2} = x - gamma (g + mu m), which is Nesterov's
+  accelerated gradient in Sutskever's look-ahead form after the change of
+  variables x = theta + mu v (pinned against that recursion).
+* ``lr_*`` schedules   - step-size rules of the experiments: halving every
+  1000 iterations (Sec. 5.1), linear warm-up then division by 10 at given
+  epochs (Sec. 5.2 / App. F.1), polynomial decay with warm-up (App. F.1).
 * ``GossipAGA``        - Algorithm 2 (App. G), the adaptive averaging period:
   a counter C of iterations since the last global average; when C reaches the
   current H the step is a global average, the minibatch losses are averaged
@@ -106,21 +114,24 @@ def beta_of(W: np.ndarray) -> float:
 # the iteration
 # ----------------------------------------------------------------------------
 
-def local_update(X, Mbuf, G, lr: float, momentum: float):
-    """m <- mu m + g ; x^{k+1/2} = x - gamma m  (Alg. 1 line 2 when mu = 0)."""
+def local_update(X, Mbuf, G, lr: float, momentum: float, nesterov: bool = False):
+    """m <- mu m + g ; x^{k+1/2} = x - gamma m  (Alg. 1 line 2 when mu = 0).
+    Nesterov variant (App. F.1): x^{k+1/2} = x - gamma (g + mu m) with the new m."""
     X = np.asarray(X, dtype=np.float64)
     G = np.asarray(G, dtype=np.float64)
     if momentum == 0.0:
         M_new = G.copy()
     else:
         M_new = momentum * np.asarray(Mbuf, dtype=np.float64) + G
+    if nesterov:
+        return X - lr * (G + momentum * M_new), M_new
     return X - lr * M_new, M_new
 
 
 def gossip_pga_step(X, Mbuf, G, k: int, *, topology: str, H: int, lr: float,
-                    momentum: float = 0.0):
+                    momentum: float = 0.0, nesterov: bool = False):
     """One iteration of Algorithm 1 in float64.  Returns (X_next, M_next)."""
-    Y, M_new = local_update(X, Mbuf, G, lr, momentum)
+    Y, M_new = local_update(X, Mbuf, G, lr, momentum, nesterov)
     if is_global_step(k, H):
         xbar = Y.mean(axis=0)                       # (1/n) sum_j x_j^{k+1/2}
         X_next = np.broadcast_to(xbar, Y.shape).copy()
@@ -138,6 +149,43 @@ def consensus_error(X) -> float:
     X = np.asarray(X, dtype=np.float64)
     D = X - X.mean(axis=0, keepdims=True)
     return float(np.sqrt(np.sum(D * D)))
+
+
+# ----------------------------------------------------------------------------
+# step-size schedules (gamma as a function of the iteration counter k)
+# ----------------------------------------------------------------------------
+
+def lr_step_decay(k: int, base: float, period: int, factor: float) -> float:
+    """gamma_k = base * factor^floor(k / period).  Sec. 5.1 runs base = 0.2,
+    factor = 1/2, period = 1000 ("decreased by half for every 1000 iterations")."""
+    return base * factor ** (k // period)
+
+
+def _warmup(k: int, base: float, warmup_iters: int, warmup_start: float):
+    """Linear warm-up: gamma rises by a constant amount per iteration from
+    ``warmup_start`` at k = 0 and reaches ``base`` at k = warmup_iters."""
+    return warmup_start + (base - warmup_start) * (k / warmup_iters)
+
+
+def lr_warmup_milestones(k: int, base: float, warmup_iters: int, warmup_start: float,
+                         milestones, factor: float) -> float:
+    """Sec. 5.2 / App. F.1: warm-up over the first iterations, then gamma is
+    multiplied by ``factor`` (1/10 in the paper) at each milestone iteration
+    (epochs 30, 60, 90 times the iterations per epoch)."""
+    if k < warmup_iters:
+        return _warmup(k, base, warmup_iters, warmup_start)
+    passed = sum(1 for m in milestones if k >= m)
+    return base * factor ** passed
+
+
+def lr_poly(k: int, base: float, warmup_iters: int, total_iters: int, power: float) -> float:
+    """App. F.1 (language modelling): warm-up from 0, then polynomial decay
+    base * (1 - (k - warmup)/(total - warmup))^power, zero from total_iters on."""
+    if k < warmup_iters:
+        return _warmup(k, base, warmup_iters, 0.0)
+    if k >= total_iters:
+        return 0.0
+    return base * (1.0 - (k - warmup_iters) / (total_iters - warmup_iters)) ** power
 
 
 # ----------------------------------------------------------------------------
@@ -335,12 +383,14 @@ class GossipPGA:
     All x_i^(0) are equal (Algorithm 1, "Require").
     """
 
-    def __init__(self, n: int, d: int, *, topology: str, H: int, lr: float,
-                 momentum: float = 0.0, x0=None, storage: str = "f32"):
+    def __init__(self, n: int, d: int, *, topology: str, H: int, lr,
+                 momentum: float = 0.0, nesterov: bool = False, x0=None, storage: str = "f32"):
         if topology not in TOPOLOGIES:
             raise ValueError(topology)
         self.n, self.d = n, d
-        self.topology, self.H, self.lr, self.momentum = topology, H, lr, momentum
+        self.topology, self.H, self.momentum = topology, H, momentum
+        self.lr = lr                      # a number, or a schedule k -> gamma_k
+        self.nesterov = nesterov
         self.storage = storage
         x0 = np.zeros(d) if x0 is None else np.asarray(x0, dtype=np.float64)
         self.X = np.tile(x0[None, :], (n, 1))
@@ -350,11 +400,17 @@ class GossipPGA:
     def _store(self, a):
         return _round_f32(a) if self.storage == "f32" else np.asarray(a, dtype=np.float64)
 
+    def lr_at(self, k: int) -> float:
+        """gamma_k; stored as float32 like every other fp32 quantity."""
+        lr = self.lr(k) if callable(self.lr) else self.lr
+        return float(np.float32(lr)) if self.storage == "f32" else float(lr)
+
     def step(self, G):
         """Consume the gradients G (n,d) of iteration k; advance to k+1."""
         G = self._store(G)
         X_next, M_next = gossip_pga_step(self.X, self.M, G, self.k, topology=self.topology,
-                                         H=self.H, lr=self.lr, momentum=self.momentum)
+                                         H=self.H, lr=self.lr_at(self.k), momentum=self.momentum,
+                                         nesterov=self.nesterov)
         self.X, self.M = self._store(X_next), self._store(M_next)
         self.k += 1
         return self.X
@@ -374,9 +430,10 @@ class GossipAGA:
     """
 
     def __init__(self, n: int, d: int, *, topology: str, H_init: int, warmup_iters: int,
-                 H_max: int, lr: float, momentum: float = 0.0, x0=None, storage: str = "f32"):
-        self.pga = GossipPGA(n, d, topology=topology, H=0, lr=lr, momentum=momentum, x0=x0,
-                             storage=storage)
+                 H_max: int, lr, momentum: float = 0.0, nesterov: bool = False, x0=None,
+                 storage: str = "f32"):
+        self.pga = GossipPGA(n, d, topology=topology, H=0, lr=lr, momentum=momentum,
+                             nesterov=nesterov, x0=x0, storage=storage)
         self.H_init, self.K_w, self.H_max = int(H_init), int(warmup_iters), int(H_max)
         self.H = int(H_init)
         self.C = 0
@@ -401,7 +458,7 @@ class GossipAGA:
         k = p.k
         self.C += 1
         G = p._store(G)
-        Y, M_next = local_update(p.X, p.M, G, p.lr, p.momentum)
+        Y, M_next = local_update(p.X, p.M, G, p.lr_at(k), p.momentum, p.nesterov)
         if self.C == self.H:
             self.C = 0
             xbar = Y.mean(axis=0)
