@@ -84,8 +84,36 @@ gpga_status gpga_bind(gpga_ctx* ctx, float* x_dev, float* x_new_dev, float* m_de
  * x0_dev (d floats on the device; NULL = zeros), m to zero and k to 0. */
 gpga_status gpga_reset(gpga_ctx* ctx, const float* x0_dev);
 
+/* Constant step size gamma from now on (detaches any schedule). */
 gpga_status gpga_set_lr(gpga_ctx* ctx, float lr);
 gpga_status gpga_set_period(gpga_ctx* ctx, int64_t H);
+
+/* Nesterov momentum as used for the image-classification runs (App. F.1):
+ * m <- momentum*m + g, x^(k+1/2) = x - lr*(g + momentum*m) with the new m.  This
+ * is Nesterov's accelerated gradient written for the look-ahead point.  on = 1
+ * needs momentum > 0 (EINVAL otherwise); on = 0 returns to heavy-ball. */
+gpga_status gpga_set_nesterov(gpga_ctx* ctx, int32_t on);
+
+/* Step-size schedules gamma_k of the paper's experiments.  gamma_k is evaluated
+ * on the host in double precision from the iteration counter k at every
+ * gpga_step / gpga_aga_step and handed to the kernel as a float.
+ *   step:       gamma_k = base_lr * factor^floor(k / period)          (Sec. 5.1:
+ *               0.2 halved every 1000 iterations)
+ *   milestones: k < warmup_iters: warmup_start_lr + (base_lr - warmup_start_lr) * k / warmup_iters;
+ *               afterwards base_lr * factor^(number of milestones <= k)  (Sec. 5.2:
+ *               warm-up over 5 epochs, divided by 10 at epochs 30, 60, 90).
+ *               milestones_host: count <= 16 iteration numbers in HOST memory, copied.
+ *   poly:       k < warmup_iters: base_lr * k / warmup_iters; k >= total_iters: 0;
+ *               else base_lr * (1 - (k - warmup_iters)/(total_iters - warmup_iters))^power
+ *               (App. F.1, language modelling: polynomial decay with warm-up).
+ * gpga_lr returns the gamma that the next step will use (-1 for a NULL context). */
+gpga_status gpga_lr_schedule_step(gpga_ctx* ctx, float base_lr, int64_t period, float factor);
+gpga_status gpga_lr_schedule_milestones(gpga_ctx* ctx, float base_lr, int64_t warmup_iters,
+                                        float warmup_start_lr, const int64_t* milestones_host,
+                                        int32_t count, float factor);
+gpga_status gpga_lr_schedule_poly(gpga_ctx* ctx, float base_lr, int64_t warmup_iters,
+                                  int64_t total_iters, float power);
+float gpga_lr(const gpga_ctx* ctx);
 /* Set the iteration counter k (resume): k drives the averaging schedule, the
  * one-peer offset and the address of synthetic gradients. */
 gpga_status gpga_set_iter(gpga_ctx* ctx, int64_t k);

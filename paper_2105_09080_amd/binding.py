@@ -32,6 +32,12 @@ SIGNATURES = [
     ("gpga_reset", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_set_lr", _c.c_int, [_ctx_p, _c.c_float]),
     ("gpga_set_period", _c.c_int, [_ctx_p, _c.c_int64]),
+    ("gpga_set_nesterov", _c.c_int, [_ctx_p, _c.c_int32]),
+    ("gpga_lr_schedule_step", _c.c_int, [_ctx_p, _c.c_float, _c.c_int64, _c.c_float]),
+    ("gpga_lr_schedule_milestones", _c.c_int, [_ctx_p, _c.c_float, _c.c_int64, _c.c_float,
+                                               _c.POINTER(_c.c_int64), _c.c_int32, _c.c_float]),
+    ("gpga_lr_schedule_poly", _c.c_int, [_ctx_p, _c.c_float, _c.c_int64, _c.c_int64, _c.c_float]),
+    ("gpga_lr", _c.c_float, [_ctx_p]),
     ("gpga_set_iter", _c.c_int, [_ctx_p, _c.c_int64]),
     ("gpga_iter", _c.c_int64, [_ctx_p]),
     ("gpga_problem_lsq", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_void_p, _c.c_int32]),
@@ -122,6 +128,30 @@ def gpga_set_lr(ctx, lr: float):
 
 def gpga_set_period(ctx, H: int):
     _check(ctx, _lib.gpga_set_period(ctx, H))
+
+
+def gpga_set_nesterov(ctx, on: bool):
+    _check(ctx, _lib.gpga_set_nesterov(ctx, int(on)))
+
+
+def gpga_lr_schedule_step(ctx, base_lr: float, period: int, factor: float):
+    _check(ctx, _lib.gpga_lr_schedule_step(ctx, base_lr, period, factor))
+
+
+def gpga_lr_schedule_milestones(ctx, base_lr: float, warmup_iters: int, warmup_start_lr: float,
+                                milestones, factor: float):
+    ms = [int(v) for v in milestones]
+    arr = (ctypes.c_int64 * max(1, len(ms)))(*ms)
+    _check(ctx, _lib.gpga_lr_schedule_milestones(ctx, base_lr, warmup_iters, warmup_start_lr, arr,
+                                                  len(ms), factor))
+
+
+def gpga_lr_schedule_poly(ctx, base_lr: float, warmup_iters: int, total_iters: int, power: float):
+    _check(ctx, _lib.gpga_lr_schedule_poly(ctx, base_lr, warmup_iters, total_iters, power))
+
+
+def gpga_lr(ctx) -> float:
+    return float(_lib.gpga_lr(ctx))
 
 
 def gpga_set_iter(ctx, k: int):

@@ -83,6 +83,40 @@ gpga_status grow_f64(gpga_ctx* c, double** p, size_t* cap, size_t need) {
     return GPGA_OK;
 }
 
+// gamma_k of the attached schedule for iteration k.
+float scheduled_lr(const gpga_ctx* c, int64_t k) {
+    double lr = c->lr;
+    switch (c->sched) {
+        case SCHED_STEP:
+            lr = c->sched_base * std::pow(c->sched_factor, (double)(k / c->sched_period));
+            break;
+        case SCHED_MILESTONES:
+            if (k < c->sched_warmup) {
+                lr = c->sched_start + (c->sched_base - c->sched_start) * ((double)k / (double)c->sched_warmup);
+            } else {
+                int passed = 0;
+                for (int j = 0; j < c->sched_count; ++j) passed += (k >= c->sched_milestones[j]);
+                lr = c->sched_base * std::pow(c->sched_factor, (double)passed);
+            }
+            break;
+        case SCHED_POLY:
+            if (k < c->sched_warmup) {
+                lr = c->sched_base * ((double)k / (double)c->sched_warmup);
+            } else if (k >= c->sched_total) {
+                lr = 0.0;
+            } else {
+                const double left = 1.0 - (double)(k - c->sched_warmup) / (double)(c->sched_total - c->sched_warmup);
+                lr = c->sched_base * std::pow(left, c->sched_power);
+            }
+            break;
+        default:
+            break;
+    }
+    return (float)lr;
+}
+
+bool finite_nonneg(float v) { return std::isfinite(v) && v >= 0.f; }
+
 gpga_status check_batch(gpga_ctx* c, const int32_t* idx, int32_t B, int32_t* Beff) {
     if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
     if (c->problem == PROB_NONE) return fail(c, GPGA_ESTATE, "no problem attached (gpga_problem_*)");
@@ -237,8 +271,63 @@ gpga_status gpga_set_lr(gpga_ctx* c, float lr) {
     if (!c) return GPGA_EINVAL;
     if (!std::isfinite(lr) || lr < 0.f) return fail(c, GPGA_EINVAL, "lr must be finite and >= 0");
     c->lr = lr;
+    c->sched = SCHED_NONE;
     return GPGA_OK;
 }
+
+gpga_status gpga_set_nesterov(gpga_ctx* c, int32_t on) {
+    if (!c) return GPGA_EINVAL;
+    if (on != 0 && on != 1) return fail(c, GPGA_EINVAL, "on must be 0 or 1");
+    if (on && c->mu == 0.f) return fail(c, GPGA_EINVAL, "Nesterov momentum needs momentum > 0");
+    c->nesterov = on != 0;
+    return GPGA_OK;
+}
+
+gpga_status gpga_lr_schedule_step(gpga_ctx* c, float base_lr, int64_t period, float factor) {
+    if (!c) return GPGA_EINVAL;
+    if (!finite_nonneg(base_lr) || !finite_nonneg(factor) || period < 1)
+        return fail(c, GPGA_EINVAL, "need base_lr >= 0, factor >= 0 (finite) and period >= 1");
+    c->sched = SCHED_STEP;
+    c->sched_base = base_lr;
+    c->sched_factor = factor;
+    c->sched_period = period;
+    return GPGA_OK;
+}
+
+gpga_status gpga_lr_schedule_milestones(gpga_ctx* c, float base_lr, int64_t warmup_iters, float warmup_start_lr,
+                                        const int64_t* milestones_host, int32_t count, float factor) {
+    if (!c) return GPGA_EINVAL;
+    if (!finite_nonneg(base_lr) || !finite_nonneg(factor) || !finite_nonneg(warmup_start_lr) || warmup_iters < 0)
+        return fail(c, GPGA_EINVAL, "need base_lr, warmup_start_lr, factor >= 0 (finite) and warmup_iters >= 0");
+    if (count < 0 || count > kMaxMilestones || (count > 0 && !milestones_host))
+        return fail(c, GPGA_EINVAL, "count must be 0..%d with a non-NULL table", kMaxMilestones);
+    for (int j = 0; j < count; ++j)
+        if (milestones_host[j] < 0) return fail(c, GPGA_EINVAL, "milestones must be >= 0");
+    c->sched = SCHED_MILESTONES;
+    c->sched_base = base_lr;
+    c->sched_factor = factor;
+    c->sched_start = warmup_start_lr;
+    c->sched_warmup = warmup_iters;
+    c->sched_count = count;
+    for (int j = 0; j < count; ++j) c->sched_milestones[j] = milestones_host[j];
+    return GPGA_OK;
+}
+
+gpga_status gpga_lr_schedule_poly(gpga_ctx* c, float base_lr, int64_t warmup_iters, int64_t total_iters,
+                                  float power) {
+    if (!c) return GPGA_EINVAL;
+    if (!finite_nonneg(base_lr) || !std::isfinite(power) || power <= 0.f || warmup_iters < 0 ||
+        total_iters <= warmup_iters)
+        return fail(c, GPGA_EINVAL, "need base_lr >= 0, power > 0 and 0 <= warmup_iters < total_iters");
+    c->sched = SCHED_POLY;
+    c->sched_base = base_lr;
+    c->sched_power = power;
+    c->sched_warmup = warmup_iters;
+    c->sched_total = total_iters;
+    return GPGA_OK;
+}
+
+float gpga_lr(const gpga_ctx* c) { return c ? scheduled_lr(c, c->k) : -1.f; }
 
 gpga_status gpga_set_period(gpga_ctx* c, int64_t H) {
     if (!c) return GPGA_EINVAL;
@@ -339,7 +428,7 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
     ge.g = c->g;
     ge.ld = c->ld;
     ge.n = c->n;
-    ge.lr = c->lr;
+    ge.lr = scheduled_lr(c, c->k);
     ge.mu = c->mu;
     const int64_t nv = vec ? c->d / 4 : 0;
     const int64_t tail = c->d - nv * 4;

@@ -21,12 +21,16 @@ enum StencilMode : int {
     MODE_SELF = 2   // cur
 };
 
+enum LrSchedule : int { SCHED_NONE = 0, SCHED_STEP, SCHED_MILESTONES, SCHED_POLY };
+constexpr int kMaxMilestones = 16;
+
 struct gpga_ctx {
     int32_t n = 0;
     int64_t d = 0;
     int32_t topo = 0;
     int64_t H = 0;
     float lr = 0.f, mu = 0.f;
+    bool nesterov = false;  // x^(k+1/2) = x - lr*(g + mu*m) instead of x - lr*m
     int64_t k = 0;
     int device = 0;
 
@@ -67,6 +71,13 @@ struct gpga_ctx {
     uint32_t pace_seq = 0;   // sequence number of paced launches
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
     unsigned long long* pace_slots = nullptr;  // 64 device words, library-owned
+
+    // step-size schedule gamma_k (evaluated on the host in double, stored as float)
+    int sched = SCHED_NONE;
+    double sched_base = 0.0, sched_factor = 1.0, sched_start = 0.0, sched_power = 1.0;
+    int64_t sched_period = 1, sched_warmup = 0, sched_total = 0;
+    int sched_count = 0;
+    int64_t sched_milestones[kMaxMilestones] = {0};
 
     // adaptive averaging period (Algorithm 2)
     bool aga = false;

@@ -2,6 +2,7 @@
 // paper's listing in Sec. 3; matrix form in App. A):
 //
 //     m_i <- mu*m_i + g_i ;  y_i = x_i - gamma*m_i              (local update)
+//     Nesterov momentum (App. F.1):  y_i = x_i - gamma*(g_i + mu*m_i)
 //     gossip :  x_new_i = sum_j w_ij y_j                         (W_k sparse)
 //     global :  x_new_i = (1/n) sum_j y_j                        (every H-th step)
 //
@@ -60,6 +61,13 @@ __device__ __forceinline__ v4f shfl_xor_t(v4f v, int off) {
     r.z = __shfl_xor(v.z, off, kWave);
     r.w = __shfl_xor(v.w, off, kWave);
     return r;
+}
+
+// x^(k+1/2) from x, the gradient and the NEW momentum value (mom = g when there is no buffer).
+template <int MOM, typename T>
+__device__ __forceinline__ T half_step(const T& xv, const T& gv, const T& mom, float lr, float mu) {
+    if (MOM == 2) return xv - lr * (gv + mu * mom);
+    return xv - lr * mom;
 }
 
 constexpr int kMaxWaves = 8;
@@ -134,7 +142,8 @@ __device__ __forceinline__ void pace_wait(const PaceArgs& p, unsigned long long 
     }
 }
 
-template <typename T, int MODE, bool MOM, int U>
+// MOM: 0 = no momentum buffer, 1 = heavy-ball, 2 = Nesterov.
+template <typename T, int MODE, int MOM, int U>
 __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     __shared__ T s_first[kMaxWaves][kWave];
@@ -205,7 +214,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 mom = mu * mv + gv;
                 st_stream(mp + (int64_t)rw * ldT, mom);
             }
-            return xv - lr * mom;
+            return half_step<MOM>(xv, gv, mom, lr, mu);
         };
         // Steady state (third row of the segment onwards): the new y completes the
         // stencil of the previous row.
@@ -333,7 +342,7 @@ struct GlobalArgs {
     PaceArgs pace;
 };
 
-template <typename T, bool MOM, int U>
+template <typename T, int MOM, int U>
 __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     __shared__ T s_part[kMaxWaves][kWave];
@@ -397,7 +406,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
                         mom = mu * b.mv[u] + b.gv[u];
                         st_stream(mp + (int64_t)(first_row + u) * ldT, mom);
                     }
-                    part += b.xv[u] - lr * mom;
+                    part += half_step<MOM>(b.xv[u], b.gv[u], mom, lr, mu);
                 }
                 sum += part;
             };
@@ -432,13 +441,14 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
             for (; done < n; ++done) {
                 const int64_t off = (int64_t)done * ldT;
                 const T xv = ld_stream(xp + off);
-                T mom = ld_stream(gp + off);
+                const T gv = ld_stream(gp + off);
+                T mom = gv;
                 if (MOM) {
-                    mom = mu * ld_stream(mp + off) + mom;
+                    mom = mu * ld_stream(mp + off) + gv;
                     st_stream(mp + off, mom);
                 }
                 units_done += kReadUnits;
-                sum += xv - lr * mom;
+                sum += half_step<MOM>(xv, gv, mom, lr, mu);
             }
         } else if (on) {
             for (int base = r0; base < n; base += RS * U) {
@@ -465,7 +475,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
                             mom = mu * mv[u] + gv[u];
                             st_stream(mp + (int64_t)row * ldT, mom);
                         }
-                        part += xv[u] - lr * mom;
+                        part += half_step<MOM>(xv[u], gv[u], mom, lr, mu);
                     }
                 }
                 sum += part;
@@ -567,7 +577,7 @@ hipError_t launch_planned(Kernel kernel, LaunchPlan plan, Args a, hipStream_t st
     return hipGetLastError();
 }
 
-template <typename T, int MODE, bool MOM>
+template <typename T, int MODE, int MOM>
 hipError_t launch_walk_u(int U, const LaunchPlan& plan, hipStream_t st, const WalkArgs& a) {
     switch (U) {
         case 1: return launch_planned(k_step_walk<T, MODE, MOM, 1>, plan, a, st);
@@ -577,7 +587,7 @@ hipError_t launch_walk_u(int U, const LaunchPlan& plan, hipStream_t st, const Wa
     }
 }
 
-template <typename T, bool MOM>
+template <typename T, int MOM>
 hipError_t launch_walk_mode(int mode, int U, const LaunchPlan& plan, hipStream_t st, const WalkArgs& a) {
     switch (mode) {
         case MODE_RING: return launch_walk_u<T, MODE_RING, MOM>(U, plan, st, a);
@@ -586,7 +596,7 @@ hipError_t launch_walk_mode(int mode, int U, const LaunchPlan& plan, hipStream_t
     }
 }
 
-template <typename T, bool MOM>
+template <typename T, int MOM>
 hipError_t launch_global_u(int U, const LaunchPlan& plan, hipStream_t st, const GlobalArgs& a) {
     switch (U) {
         case 1: return launch_planned(k_step_global<T, MOM, 1>, plan, a, st);
@@ -677,13 +687,15 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= 8, kAutoPaceGbsWalk);
     // paced wavefronts advance one row per batch (two rows in flight); free-running ones two
     const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : kDefaultUnroll);
-    const bool mom = c->mu != 0.f;
+    const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     if (vec == 4) {
-        return mom ? launch_walk_mode<v4f, true>(mode, U, plan, c->stream, a)
-                   : launch_walk_mode<v4f, false>(mode, U, plan, c->stream, a);
+        if (mom == 2) return launch_walk_mode<v4f, 2>(mode, U, plan, c->stream, a);
+        return mom ? launch_walk_mode<v4f, 1>(mode, U, plan, c->stream, a)
+                   : launch_walk_mode<v4f, 0>(mode, U, plan, c->stream, a);
     }
-    return mom ? launch_walk_mode<float, true>(mode, U, plan, c->stream, a)
-               : launch_walk_mode<float, false>(mode, U, plan, c->stream, a);
+    if (mom == 2) return launch_walk_mode<float, 2>(mode, U, plan, c->stream, a);
+    return mom ? launch_walk_mode<float, 1>(mode, U, plan, c->stream, a)
+               : launch_walk_mode<float, 0>(mode, U, plan, c->stream, a);
 }
 
 hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
@@ -720,11 +732,13 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     a.xcd = c->opt_xcd_swizzle;
     const LaunchPlan plan = make_plan(c, gx, waves, vec, RL == 1 && wpb == 1 && n >= 8, kAutoPaceGbsGlobal);
     const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : 4);
-    const bool mom = c->mu != 0.f;
+    const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     if (vec == 4) {
-        return mom ? launch_global_u<v4f, true>(U, plan, c->stream, a)
-                   : launch_global_u<v4f, false>(U, plan, c->stream, a);
+        if (mom == 2) return launch_global_u<v4f, 2>(U, plan, c->stream, a);
+        return mom ? launch_global_u<v4f, 1>(U, plan, c->stream, a)
+                   : launch_global_u<v4f, 0>(U, plan, c->stream, a);
     }
-    return mom ? launch_global_u<float, true>(U, plan, c->stream, a)
-               : launch_global_u<float, false>(U, plan, c->stream, a);
+    if (mom == 2) return launch_global_u<float, 2>(U, plan, c->stream, a);
+    return mom ? launch_global_u<float, 1>(U, plan, c->stream, a)
+               : launch_global_u<float, 0>(U, plan, c->stream, a);
 }

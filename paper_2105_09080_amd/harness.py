@@ -116,6 +116,14 @@ class Simulation:
     def step(self):
         B.gpga_step(self.ctx)
 
+    def set_nesterov(self, on: bool = True):
+        B.gpga_set_nesterov(self.ctx, on)
+
+    @property
+    def lr(self) -> float:
+        """Step size the next step will use."""
+        return B.gpga_lr(self.ctx)
+
     def aga_enable(self, H_init: int, warmup_iters: int, H_max: int):
         B.gpga_aga_enable(self.ctx, H_init, warmup_iters, H_max)
 
