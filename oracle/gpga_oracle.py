@@ -16,6 +16,9 @@ What each function follows (Gossip-PGA paper, arXiv 2105.09080):
   Ring: |N_i| = 3 (Sec. 3.3 cost model) with uniform weights 1/3, the reading
   that reproduces the beta values printed in Sec. 5.1.  One-peer exponential
   graph: App. F.1 (time-varying, one peer per iteration, equal weights).
+  Grid: |N_i| = 5 (Sec. 3.3) on a torus with weights 1/5 (1 - beta = O(1/n));
+  static exponential graph (App. F.2 figures): self plus the ceil(log2 n)
+  power-of-two offsets with equal weights; ``custom``: any dense W.
 * ``consensus_error``  - ||X - Xbar||_F, the consensus distance of Sec. 4 /
   App. B.  ``node_mean`` - xbar = (1/n) sum_i x_i (App. A notation).
 * ``logreg_loss/grad`` - the logistic loss of Sec. 5.1,
@@ -63,7 +66,7 @@ from scipy.special import expit
 # schedule and topology
 # ----------------------------------------------------------------------------
 
-TOPOLOGIES = ("ring", "expo1", "none", "full")
+TOPOLOGIES = ("ring", "expo1", "none", "full", "grid", "expo", "custom")
 
 
 def is_global_step(k: int, H: int) -> bool:
@@ -82,6 +85,15 @@ def one_peer_shift(n: int, k: int) -> int:
     return (1 << (k % one_peer_tau(n))) % n
 
 
+def grid_shape(n: int):
+    """The most nearly square r x c factorisation of n (r <= c, r the largest
+    divisor of n not above sqrt(n)); a prime n gives 1 x n."""
+    r = int(math.isqrt(n))
+    while n % r:
+        r -= 1
+    return r, n // r
+
+
 def mixing_matrix(topology: str, n: int, k: int = 0) -> np.ndarray:
     """Dense float64 W_k with w_ij = weight of node j's iterate in node i's mix."""
     W = np.zeros((n, n), dtype=np.float64)
@@ -95,6 +107,24 @@ def mixing_matrix(topology: str, n: int, k: int = 0) -> np.ndarray:
         for i in range(n):
             W[i, i] += 0.5
             W[i, (i + s) % n] += 0.5
+    elif topology == "grid":
+        # |N_i| = 5 (Sec. 3.3): node (a, b) of an r x c grid, numbered a*c + b, with its
+        # four neighbours (a +- 1, b), (a, b +- 1); indices wrap (torus) so that every
+        # node has the same neighbourhood size, weight 1/5 each.  1 - beta = O(1/n).
+        r, c = grid_shape(n)
+        for a in range(r):
+            for b in range(c):
+                i = a * c + b
+                for aa, bb in ((a, b), (a - 1, b), (a + 1, b), (a, b - 1), (a, b + 1)):
+                    W[i, (aa % r) * c + (bb % c)] += 1.0 / 5.0
+    elif topology == "expo":
+        # static exponential graph: node i hears from i + 2^0, i + 2^1, ..., i + 2^(tau-1)
+        # (mod n) and itself, tau = ceil(log2 n), equal weights 1/(tau + 1)
+        tau = one_peer_tau(n)
+        for i in range(n):
+            W[i, i] += 1.0 / (tau + 1)
+            for j in range(tau):
+                W[i, (i + (1 << j)) % n] += 1.0 / (tau + 1)
     elif topology == "none":      # W = I : Local SGD
         W[np.arange(n), np.arange(n)] = 1.0
     elif topology == "full":      # W = (1/n) 1 1^T : parallel SGD
@@ -129,14 +159,16 @@ def local_update(X, Mbuf, G, lr: float, momentum: float, nesterov: bool = False)
 
 
 def gossip_pga_step(X, Mbuf, G, k: int, *, topology: str, H: int, lr: float,
-                    momentum: float = 0.0, nesterov: bool = False):
-    """One iteration of Algorithm 1 in float64.  Returns (X_next, M_next)."""
+                    momentum: float = 0.0, nesterov: bool = False, W=None):
+    """One iteration of Algorithm 1 in float64.  Returns (X_next, M_next).
+    ``topology='custom'`` mixes with the given dense W (any doubly stochastic matrix)."""
     Y, M_new = local_update(X, Mbuf, G, lr, momentum, nesterov)
     if is_global_step(k, H):
         xbar = Y.mean(axis=0)                       # (1/n) sum_j x_j^{k+1/2}
         X_next = np.broadcast_to(xbar, Y.shape).copy()
     else:
-        X_next = mixing_matrix(topology, Y.shape[0], k) @ Y
+        Wk = np.asarray(W, dtype=np.float64) if topology == "custom" else mixing_matrix(topology, Y.shape[0], k)
+        X_next = Wk @ Y
     return X_next, M_new
 
 
@@ -384,9 +416,12 @@ class GossipPGA:
     """
 
     def __init__(self, n: int, d: int, *, topology: str, H: int, lr,
-                 momentum: float = 0.0, nesterov: bool = False, x0=None, storage: str = "f32"):
+                 momentum: float = 0.0, nesterov: bool = False, x0=None, storage: str = "f32", W=None):
         if topology not in TOPOLOGIES:
             raise ValueError(topology)
+        if (topology == "custom") != (W is not None):
+            raise ValueError("a dense W goes with topology='custom' and only with it")
+        self.W = None if W is None else np.asarray(W, dtype=np.float64)
         self.n, self.d = n, d
         self.topology, self.H, self.momentum = topology, H, momentum
         self.lr = lr                      # a number, or a schedule k -> gamma_k
@@ -410,7 +445,7 @@ class GossipPGA:
         G = self._store(G)
         X_next, M_next = gossip_pga_step(self.X, self.M, G, self.k, topology=self.topology,
                                          H=self.H, lr=self.lr_at(self.k), momentum=self.momentum,
-                                         nesterov=self.nesterov)
+                                         nesterov=self.nesterov, W=self.W)
         self.X, self.M = self._store(X_next), self._store(M_next)
         self.k += 1
         return self.X
@@ -472,7 +507,8 @@ class GossipAGA:
                 self.H = int(min(max(H_new, 1), self.H_max))
             self.history.append((k, self.H))
         else:
-            X_next = mixing_matrix(p.topology, p.n, k) @ Y
+            Wk = p.W if p.topology == "custom" else mixing_matrix(p.topology, p.n, k)
+            X_next = Wk @ Y
         p.X, p.M = p._store(X_next), p._store(M_next)
         p.k += 1
         return p.X
