@@ -53,7 +53,14 @@ typedef enum {
                             iteration k row i averages with row (i + 2^(k mod tau)) mod n,
                             tau = ceil(log2 n), weights 1/2                             */
     GPGA_TOPO_NONE = 2,  /* W = I                                                        */
-    GPGA_TOPO_FULL = 3   /* W = (1/n) 1 1^T : every step is a global average             */
+    GPGA_TOPO_FULL = 3,  /* W = (1/n) 1 1^T : every step is a global average             */
+    GPGA_TOPO_GRID = 4,  /* grid, |N_i| = 5 (Sec. 3.3; 1 - beta = O(1/n)): node a*c + b of the
+                            most nearly square r x c factorisation of n (r <= c) mixes itself
+                            and (a +- 1, b), (a, b +- 1), indices mod r / mod c, weights 1/5;
+                            coinciding neighbours (r or c below 3) add their weights          */
+    GPGA_TOPO_EXPO = 5,  /* static exponential graph (App. F.2): row i mixes itself and rows
+                            i + 2^j mod n, j = 0..tau-1, tau = ceil(log2 n), weights 1/(tau+1)  */
+    GPGA_TOPO_CUSTOM = 6 /* any doubly stochastic W, attached with gpga_set_mixing_csr         */
 } gpga_topology;
 
 /* Algorithm 1 "Require": learning rate gamma = lr > 0 (finite), weight matrix
@@ -166,6 +173,31 @@ gpga_status gpga_local_loss(gpga_ctx* ctx, const int32_t* batch_idx_dev, int32_t
  * m and x_new once; then swaps x / x_new and increments k. */
 gpga_status gpga_step(gpga_ctx* ctx);
 
+/* Attach an arbitrary weight matrix W (Sec. 3: W >= 0, W 1 = 1, 1^T W = 1^T,
+ * w_ij > 0 only for neighbours and i = j) in compressed-row form and switch the
+ * context to GPGA_TOPO_CUSTOM.  All three arrays are in HOST memory and are
+ * copied: row_ptr_host has n+1 entries (row_ptr[0] = 0), row i owns entries
+ * row_ptr[i] .. row_ptr[i+1]-1 of col_host (node j) and val_host (w_ij, fp32).
+ * EINVAL if an index is out of range, a weight is negative or not finite, or a
+ * row or column sum differs from 1 by more than 1e-5.  Synchronises the stream.
+ * Gossip steps with GRID, EXPO and CUSTOM run as one fused kernel (the column
+ * tile of all n rows staged in LDS, 20 B per element) for n <= 256; above that
+ * they run as a local-update pass that OVERWRITES g_dev with x^(k+1/2), followed
+ * by a sparse product. */
+gpga_status gpga_set_mixing_csr(gpga_ctx* ctx, const int64_t* row_ptr_host, const int32_t* col_host,
+                                const float* val_host);
+
+/* Connectivity beta = ||W - (1/n) 1 1^T||_2 (Assumption 3) of the context's
+ * current W (for the one-peer graph: the matrix of the current iteration),
+ * computed on the host by Lanczos iteration in double precision. */
+gpga_status gpga_mixing_beta(gpga_ctx* ctx, double* beta_out);
+/* The same for a named graph (not CUSTOM) without a context or a device. */
+gpga_status gpga_topology_beta(int32_t topology, int32_t n, int64_t k, double* beta_out);
+/* Validates host CSR arrays exactly as gpga_set_mixing_csr does (EINVAL if W is
+ * rejected) and, if beta_out is not NULL, stores its beta.  Needs no device. */
+gpga_status gpga_check_mixing_csr(int32_t n, const int64_t* row_ptr_host, const int32_t* col_host,
+                                  const float* val_host, double* beta_out);
+
 /* Adaptive averaging period, Gossip-AGA (Algorithm 2, App. G).  After
  * gpga_aga_enable the period starts at H_init and iterations are advanced with
  * gpga_aga_step instead of gpga_step: a counter C of iterations since the last
@@ -198,6 +230,7 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * sharing one column tile along the node axis, 0 = automatic, else 1, 2, 4, 8;
  * must not exceed "waves"), "row_lanes" (global-average kernel: lanes of a
  * wavefront spread over rows: 0 = automatic, 1, 2, 4), "xcd_swizzle" (0/1),
+ * "mix_two_pass" (1 = sparse-W gossip steps always take the two-pass path),
  * "blocks_per_cu" (persistent launch of the fused step: -1 = automatic, 0 = one
  * workgroup per column-tile group, k = 1..32 resident workgroups per compute unit,
  * each striding over the tile groups), "pace_gbs" (target rate in GB/s of paced

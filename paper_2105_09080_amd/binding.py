@@ -16,8 +16,10 @@ LIB_PATH = os.path.join(_PKG_DIR, "libgpga.so")
 
 GPGA_OK, GPGA_EINVAL, GPGA_ENOMEM, GPGA_EDEVICE, GPGA_ESTATE = 0, 1, 2, 3, 4
 GPGA_TOPO_RING, GPGA_TOPO_EXPO1, GPGA_TOPO_NONE, GPGA_TOPO_FULL = 0, 1, 2, 3
+GPGA_TOPO_GRID, GPGA_TOPO_EXPO, GPGA_TOPO_CUSTOM = 4, 5, 6
 TOPOLOGY = {"ring": GPGA_TOPO_RING, "expo1": GPGA_TOPO_EXPO1, "none": GPGA_TOPO_NONE,
-            "full": GPGA_TOPO_FULL}
+            "full": GPGA_TOPO_FULL, "grid": GPGA_TOPO_GRID, "expo": GPGA_TOPO_EXPO,
+            "custom": GPGA_TOPO_CUSTOM}
 _STATUS_NAME = {0: "GPGA_OK", 1: "GPGA_EINVAL", 2: "GPGA_ENOMEM", 3: "GPGA_EDEVICE", 4: "GPGA_ESTATE"}
 
 #: every symbol include/gpga.h declares: (name, restype, argtypes)
@@ -47,6 +49,12 @@ SIGNATURES = [
     ("gpga_local_grad", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int32]),
     ("gpga_local_loss", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int32, _c.c_void_p]),
     ("gpga_step", _c.c_int, [_ctx_p]),
+    ("gpga_set_mixing_csr", _c.c_int, [_ctx_p, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int32),
+                                       _c.POINTER(_c.c_float)]),
+    ("gpga_mixing_beta", _c.c_int, [_ctx_p, _c.POINTER(_c.c_double)]),
+    ("gpga_topology_beta", _c.c_int, [_c.c_int32, _c.c_int32, _c.c_int64, _c.POINTER(_c.c_double)]),
+    ("gpga_check_mixing_csr", _c.c_int, [_c.c_int32, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int32),
+                                         _c.POINTER(_c.c_float), _c.POINTER(_c.c_double)]),
     ("gpga_aga_enable", _c.c_int, [_ctx_p, _c.c_int64, _c.c_int64, _c.c_int64]),
     ("gpga_aga_step", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_period", _c.c_int64, [_ctx_p]),
@@ -188,6 +196,45 @@ def gpga_local_loss(ctx, batch_idx, B: int, loss):
 
 def gpga_step(ctx):
     _check(ctx, _lib.gpga_step(ctx))
+
+
+def _csr_arrays(row_ptr, col, val):
+    rp = [int(v) for v in row_ptr]
+    cl = [int(v) for v in col]
+    vl = [float(v) for v in val]
+    return ((ctypes.c_int64 * len(rp))(*rp), (ctypes.c_int32 * max(1, len(cl)))(*cl),
+            (ctypes.c_float * max(1, len(vl)))(*vl))
+
+
+def gpga_set_mixing_csr(ctx, row_ptr, col, val):
+    """row_ptr (n+1), col, val: host sequences (lists or NumPy arrays)."""
+    rp, cl, vl = _csr_arrays(row_ptr, col, val)
+    _check(ctx, _lib.gpga_set_mixing_csr(ctx, rp, cl, vl))
+
+
+def gpga_mixing_beta(ctx) -> float:
+    out = ctypes.c_double()
+    _check(ctx, _lib.gpga_mixing_beta(ctx, ctypes.byref(out)))
+    return out.value
+
+
+def gpga_topology_beta(topology, n: int, k: int = 0) -> float:
+    topo = TOPOLOGY[topology] if isinstance(topology, str) else int(topology)
+    out = ctypes.c_double()
+    status = _lib.gpga_topology_beta(topo, n, k, ctypes.byref(out))
+    if status != GPGA_OK:
+        raise GpgaError(status, "gpga_topology_beta rejected its arguments")
+    return out.value
+
+
+def gpga_check_mixing_csr(n: int, row_ptr, col, val) -> float:
+    """Validates W; returns its beta.  Raises GpgaError(EINVAL) if W is rejected."""
+    rp, cl, vl = _csr_arrays(row_ptr, col, val)
+    out = ctypes.c_double()
+    status = _lib.gpga_check_mixing_csr(n, rp, cl, vl, ctypes.byref(out))
+    if status != GPGA_OK:
+        raise GpgaError(status, "mixing matrix rejected")
+    return out.value
 
 
 def gpga_aga_enable(ctx, H_init: int, warmup_iters: int, H_max: int):

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libgpga.so")
-SOURCES = ["gpga_api.hip", "gpga_step.hip", "gpga_grad.hip", "gpga_reduce.hip"]
+SOURCES = ["gpga_api.hip", "gpga_step.hip", "gpga_mix.hip", "gpga_graph.hip", "gpga_grad.hip", "gpga_reduce.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

@@ -117,6 +117,71 @@ float scheduled_lr(const gpga_ctx* c, int64_t k) {
 
 bool finite_nonneg(float v) { return std::isfinite(v) && v >= 0.f; }
 
+bool is_csr_topology(int topo) {
+    return topo == GPGA_TOPO_GRID || topo == GPGA_TOPO_EXPO || topo == GPGA_TOPO_CUSTOM;
+}
+
+void free_csr_device(gpga_ctx* c) {
+    if (c->csr_ptr_d) (void)hipFree(c->csr_ptr_d);
+    if (c->csr_col_d) (void)hipFree(c->csr_col_d);
+    if (c->csr_val_d) (void)hipFree(c->csr_val_d);
+    c->csr_ptr_d = nullptr;
+    c->csr_col_d = nullptr;
+    c->csr_val_d = nullptr;
+    c->csr_ready = false;
+}
+
+// Copies c->csr to the device (synchronous; set-up time only).
+gpga_status upload_csr(gpga_ctx* c) {
+    if (c->bound) {
+        const hipError_t e = hipStreamSynchronize(c->stream);  // a running step may still read the old copy
+        if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+    }
+    free_csr_device(c);
+    const size_t np = c->csr.ptr.size(), nz = c->csr.col.size();
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->csr_ptr_d), np * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->csr_col_d), (nz ? nz : 1) * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->csr_val_d), (nz ? nz : 1) * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(c->csr_ptr_d, c->csr.ptr.data(), np * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess && nz) e = hipMemcpy(c->csr_col_d, c->csr.col.data(), nz * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess && nz) e = hipMemcpy(c->csr_val_d, c->csr.val.data(), nz * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        free_csr_device(c);
+        return hip_fail(c, e, "mixing matrix upload");
+    }
+    c->csr_ready = true;
+    return GPGA_OK;
+}
+
+// W of a named graph at iteration k as a host CSR; false for graphs without a sparse form here.
+bool named_graph_csr(int32_t topo, int32_t n, int64_t k, HostCsr* out) {
+    switch (topo) {
+        case GPGA_TOPO_RING: build_ring_csr(n, out); return true;
+        case GPGA_TOPO_EXPO1: build_one_peer_csr(n, (int32_t)((1LL << (k % tau_of(n))) % n), out); return true;
+        case GPGA_TOPO_NONE: build_one_peer_csr(n, 0, out); return true;  // 1/2 + 1/2 on the diagonal
+        case GPGA_TOPO_GRID: build_grid_csr(n, out); return true;
+        case GPGA_TOPO_EXPO: build_static_expo_csr(n, out); return true;
+        default: return false;
+    }
+}
+
+// Copies a caller's CSR arrays after range checks on the row pointers.
+const char* copy_csr(int32_t n, const int64_t* row_ptr, const int32_t* col, const float* val, HostCsr* out) {
+    if (!row_ptr || row_ptr[0] != 0) return "row_ptr must start at 0";
+    for (int32_t i = 0; i < n; ++i)
+        if (row_ptr[i + 1] < row_ptr[i]) return "row_ptr must be non-decreasing";
+    const int64_t nnz = row_ptr[n];
+    if (nnz < n || nnz > 0x7fffffffLL) return "W needs between n and 2^31-1 entries";
+    if (!col || !val) return "col and val must not be NULL";
+    out->ptr.resize((size_t)n + 1);
+    for (int32_t i = 0; i <= n; ++i) out->ptr[i] = (int32_t)row_ptr[i];
+    out->col.assign(col, col + nnz);
+    out->val.assign(val, val + nnz);
+    return nullptr;
+}
+
+constexpr double kStochasticTol = 1e-5;  // |row / column sum - 1| allowed for fp32 weights
+
 gpga_status check_batch(gpga_ctx* c, const int32_t* idx, int32_t B, int32_t* Beff) {
     if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
     if (c->problem == PROB_NONE) return fail(c, GPGA_ESTATE, "no problem attached (gpga_problem_*)");
@@ -179,7 +244,7 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
     *out = nullptr;
     if (n < 1 || n > (1 << 24)) return GPGA_EINVAL;
     if (d < 1 || d > (int64_t)0xffffffffLL * 4) return GPGA_EINVAL;  // column quad index is 32-bit
-    if (topology < GPGA_TOPO_RING || topology > GPGA_TOPO_FULL) return GPGA_EINVAL;
+    if (topology < GPGA_TOPO_RING || topology > GPGA_TOPO_CUSTOM) return GPGA_EINVAL;
     if (H < 0) return GPGA_EINVAL;
     if (!std::isfinite(lr) || lr < 0.f) return GPGA_EINVAL;
     if (!(momentum >= 0.f && momentum < 1.f)) return GPGA_EINVAL;
@@ -219,6 +284,13 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
         delete c;
         return GPGA_ENOMEM;
     }
+    if (topology == GPGA_TOPO_GRID || topology == GPGA_TOPO_EXPO) {
+        named_graph_csr(topology, n, 0, &c->csr);
+        if (upload_csr(c) != GPGA_OK) {
+            (void)gpga_destroy(c);
+            return GPGA_ENOMEM;
+        }
+    }
     *out = c;
     return GPGA_OK;
 }
@@ -231,6 +303,7 @@ gpga_status gpga_destroy(gpga_ctx* c) {
     if (c->coef) (void)hipFree(c->coef);
     if (c->partials) (void)hipFree(c->partials);
     if (c->pace_slots) (void)hipFree(c->pace_slots);
+    free_csr_device(c);
     if (c->host_scalar) (void)hipHostFree(c->host_scalar);
     delete c;
     return s;
@@ -419,6 +492,10 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
         }
     }
 
+    const bool csr = !global && c->n > 1 && is_csr_topology(c->topo);
+    if (csr && !c->csr_ready)
+        return fail(c, GPGA_ESTATE, "no mixing matrix attached (gpga_set_mixing_csr)");
+
     const bool vec = aligned(c->x, 16) && aligned(c->x_new, 16) && aligned(c->g, 16) &&
                      (!c->m || aligned(c->m, 16)) && (c->ld % 4 == 0);
     StepGeom ge;
@@ -438,7 +515,8 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
         ge.ncols = pass == 0 ? nv : tail;
         if (ge.ncols == 0) continue;
         const int v = pass == 0 ? 4 : 1;
-        e = global ? launch_step_global(c, ge, v) : launch_step_walk(c, ge, mode, S, v);
+        e = global ? launch_step_global(c, ge, v)
+                   : csr ? launch_step_csr(c, ge, v) : launch_step_walk(c, ge, mode, S, v);
     }
     if (e != hipSuccess) return hip_fail(c, e, "step kernel launch");
     float* t = c->x;
@@ -455,6 +533,62 @@ gpga_status gpga_step(gpga_ctx* c) {
     DeviceGuard guard(c->device);
     const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
     return run_step(c, global);
+}
+
+gpga_status gpga_set_mixing_csr(gpga_ctx* c, const int64_t* row_ptr_host, const int32_t* col_host,
+                                const float* val_host) {
+    if (!c) return GPGA_EINVAL;
+    HostCsr w;
+    const char* why = copy_csr(c->n, row_ptr_host, col_host, val_host, &w);
+    if (!why) why = validate_csr(c->n, w, kStochasticTol);
+    if (why) return fail(c, GPGA_EINVAL, "mixing matrix rejected: %s", why);
+    DeviceGuard guard(c->device);
+    c->csr = w;
+    const gpga_status s = upload_csr(c);
+    if (s != GPGA_OK) return s;
+    c->topo = GPGA_TOPO_CUSTOM;
+    return GPGA_OK;
+}
+
+gpga_status gpga_mixing_beta(gpga_ctx* c, double* beta_out) {
+    if (!c) return GPGA_EINVAL;
+    if (!beta_out) return fail(c, GPGA_EINVAL, "beta_out must not be NULL");
+    if (c->topo == GPGA_TOPO_FULL) {
+        *beta_out = 0.0;
+        return GPGA_OK;
+    }
+    if (is_csr_topology(c->topo)) {
+        if (!c->csr_ready) return fail(c, GPGA_ESTATE, "no mixing matrix attached (gpga_set_mixing_csr)");
+        *beta_out = mixing_beta(c->n, c->csr);
+        return GPGA_OK;
+    }
+    HostCsr w;
+    named_graph_csr(c->topo, c->n, c->k, &w);
+    *beta_out = mixing_beta(c->n, w);
+    return GPGA_OK;
+}
+
+gpga_status gpga_topology_beta(int32_t topology, int32_t n, int64_t k, double* beta_out) {
+    if (!beta_out || n < 1 || n > (1 << 24) || k < 0) return GPGA_EINVAL;
+    if (topology == GPGA_TOPO_FULL) {
+        *beta_out = 0.0;
+        return GPGA_OK;
+    }
+    HostCsr w;
+    if (!named_graph_csr(topology, n, k, &w)) return GPGA_EINVAL;
+    *beta_out = mixing_beta(n, w);
+    return GPGA_OK;
+}
+
+gpga_status gpga_check_mixing_csr(int32_t n, const int64_t* row_ptr_host, const int32_t* col_host,
+                                  const float* val_host, double* beta_out) {
+    if (n < 1 || n > (1 << 24)) return GPGA_EINVAL;
+    HostCsr w;
+    const char* why = copy_csr(n, row_ptr_host, col_host, val_host, &w);
+    if (!why) why = validate_csr(n, w, kStochasticTol);
+    if (why) return GPGA_EINVAL;
+    if (beta_out) *beta_out = mixing_beta(n, w);
+    return GPGA_OK;
 }
 
 gpga_status gpga_aga_enable(gpga_ctx* c, int64_t H_init, int64_t warmup_iters, int64_t H_max) {
@@ -560,6 +694,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "xcd_swizzle")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
         c->opt_xcd_swizzle = (int)value;
+    } else if (!strcmp(name, "mix_two_pass")) {
+        if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_two_pass must be 0 or 1");
+        c->opt_mix_two_pass = (int)value;
     } else if (!strcmp(name, "pace_gbs")) {
         if (value < -1 || value > 16000) return fail(c, GPGA_EINVAL, "pace_gbs must be -1 (automatic), 0 (off) or a rate up to 16000 GB/s");
         c->opt_pace_gbs = (int)value;

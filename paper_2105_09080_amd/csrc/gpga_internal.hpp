@@ -6,9 +6,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "gpga.h"
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;  // gfx950 wavefront width
 
@@ -19,6 +22,14 @@ enum StencilMode : int {
     MODE_RING = 0,  // (prev + cur + next) / 3
     MODE_PEER = 1,  // (cur + next) / 2
     MODE_SELF = 2   // cur
+};
+
+// A sparse mixing matrix W in compressed-row form: row i lists the nodes j whose
+// iterates node i mixes (w_ij > 0) and their weights.
+struct HostCsr {
+    std::vector<int32_t> ptr;  // n + 1
+    std::vector<int32_t> col;
+    std::vector<float> val;
 };
 
 enum LrSchedule : int { SCHED_NONE = 0, SCHED_STEP, SCHED_MILESTONES, SCHED_POLY };
@@ -65,12 +76,20 @@ struct gpga_ctx {
     int opt_row_split = 0;
     int opt_row_lanes = 0;
     int opt_xcd_swizzle = 0;
+    int opt_mix_two_pass = 0;  // 1 = sparse-W steps always take the two-pass path
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
     int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
     uint32_t pace_seq = 0;   // sequence number of paced launches
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
     unsigned long long* pace_slots = nullptr;  // 64 device words, library-owned
+
+    // sparse mixing matrix of the grid / static exponential / custom graphs
+    HostCsr csr;                 // host copy (also used by the beta estimate)
+    int32_t* csr_ptr_d = nullptr;  // device copies, library-owned
+    int32_t* csr_col_d = nullptr;
+    float* csr_val_d = nullptr;
+    bool csr_ready = false;
 
     // step-size schedule gamma_k (evaluated on the host in double, stored as float)
     int sched = SCHED_NONE;
@@ -106,6 +125,23 @@ struct StepGeom {
 hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec);
 // Global-average step.
 hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec);
+
+// Gossip step with a sparse W in CSR form (c->csr_*_d): one fused kernel with the
+// column tile of all n rows staged in LDS when it fits, else local update into
+// the g buffer followed by a sparse product.
+hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec);
+
+// Host-side graph construction and analysis.
+void build_ring_csr(int32_t n, HostCsr* out);
+void build_one_peer_csr(int32_t n, int32_t shift, HostCsr* out);
+void build_grid_csr(int32_t n, HostCsr* out);
+void build_static_expo_csr(int32_t n, HostCsr* out);
+// Checks shape, index range, non-negativity and row / column sums (|sum - 1| <= tol).
+// Returns nullptr when W is acceptable, else a static description of the defect.
+const char* validate_csr(int32_t n, const HostCsr& w, double tol);
+// beta = ||W - (1/n) 1 1^T||_2 (Assumption 3) by Lanczos iteration on W^T W restricted
+// to the complement of the all-ones vector.
+double mixing_beta(int32_t n, const HostCsr& w);
 
 // Gradients.
 hipError_t launch_synth_grad(const gpga_ctx* c);

@@ -1,0 +1,220 @@
+// Gossip step with a general sparse weight matrix W (grid, static exponential
+// graph, caller-supplied W), Algorithm 1 of the paper with the matrix form of
+// App. A:   X_new = W (X - gamma * M'),   M' = mu*M + G.
+//
+// W is held in compressed-row form: row i lists the neighbours j in N_i and the
+// weights w_ij (Sec. 3).  Mixing acts along the node axis only, so a column
+// tile of ALL n rows is self-contained:
+//
+//  * fused tile kernel (n*tile bytes fit in 64 KiB of LDS): a workgroup of four
+//    wavefronts owns one column tile (64 lanes x 16 / 8 / 4 bytes).  Phase 1: the
+//    waves share the rows, read x, m, g once (coalesced row segments), store the
+//    new m and put y = x^(k+1/2) into LDS.  Phase 2: each wave produces its share
+//    of output rows as sum_j w_ij y_j from LDS and streams them to x_new.  Every
+//    element of x, m, g is read from HBM once and m, x_new written once (20 B per
+//    element), exactly like the ring / one-peer stencil kernels.
+//  * two-pass path (more rows than LDS can hold): pass 1 is the elementwise local
+//    update, which overwrites g with y (g is consumed by the step anyway);
+//    pass 2 is the sparse product x_new = W y with workgroups ordered so that
+//    all rows of a column tile run together and re-reads of y hit the caches
+//    (28 B per element of HBM traffic when they do).
+#include "gpga_internal.hpp"
+
+namespace {
+
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T* p) {
+    return __builtin_nontemporal_load(p);
+}
+template <typename T>
+__device__ __forceinline__ void st_stream(T* p, T v) {
+    __builtin_nontemporal_store(v, p);
+}
+
+// x^(k+1/2) from x, g and the new momentum value (MOM: 0 none, 1 heavy-ball, 2 Nesterov).
+template <int MOM, typename T>
+__device__ __forceinline__ T half_step(const T& xv, const T& gv, const T& mom, float lr, float mu) {
+    if (MOM == 2) return xv - lr * (gv + mu * mom);
+    return xv - lr * mom;
+}
+
+struct CsrDev {
+    const int32_t* ptr;
+    const int32_t* col;
+    const float* val;
+};
+
+struct TileArgs {
+    StepGeom ge;
+    CsrDev w;
+};
+
+constexpr int kTileWaves = 4;
+constexpr int kTileUnroll = 4;
+constexpr size_t kTileLdsBytes = 64 * 1024;
+
+template <typename T, int MOM>
+__global__ void __launch_bounds__(kWave* kTileWaves) k_step_tile(const TileArgs a) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    T* __restrict__ sy = reinterpret_cast<T*>(s_raw);  // [n][kWave]
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = a.ge.n;
+    const int64_t ldT = a.ge.ld / V;
+    const float lr = a.ge.lr, mu = a.ge.mu;
+    const int64_t col = (int64_t)blockIdx.x * kWave + lane;
+    const bool on = col < a.ge.ncols;
+
+    const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+    const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+    T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+    T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+
+    // Phase 1: rows wave, wave + 4, ... : local update, y into LDS.
+    for (int base = wave; base < n; base += kTileWaves * kTileUnroll) {
+        T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
+#pragma unroll
+        for (int u = 0; u < kTileUnroll; ++u) {
+            const int row = base + u * kTileWaves;
+            if (row < n && on) {
+                const int64_t off = (int64_t)row * ldT;
+                xv[u] = ld_stream(xp + off);
+                if (MOM) mv[u] = ld_stream(mp + off);
+                gv[u] = ld_stream(gp + off);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kTileUnroll; ++u) {
+            const int row = base + u * kTileWaves;
+            if (row < n) {
+                T y = T(0);
+                if (on) {
+                    T mom = gv[u];
+                    if (MOM) {
+                        mom = mu * mv[u] + gv[u];
+                        st_stream(mp + (int64_t)row * ldT, mom);
+                    }
+                    y = half_step<MOM>(xv[u], gv[u], mom, lr, mu);
+                }
+                sy[row * kWave + lane] = y;
+            }
+        }
+    }
+    __syncthreads();
+    // Phase 2: output rows wave, wave + 4, ... from the staged y.
+    if (!on) return;
+    for (int i = wave; i < n; i += kTileWaves) {
+        const int p0 = a.w.ptr[i], p1 = a.w.ptr[i + 1];
+        T acc = T(0);
+        for (int p = p0; p < p1; ++p) acc += a.w.val[p] * sy[a.w.col[p] * kWave + lane];
+        st_stream(xnp + (int64_t)i * ldT, acc);
+    }
+}
+
+// Two-pass path, pass 1: m <- mu m + g, y = x^(k+1/2) written over g.
+template <typename T, int MOM>
+__global__ void __launch_bounds__(256) k_update_y(const StepGeom ge, float* y_out) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    const int64_t ldT = ge.ld / V;
+    const int64_t total = (int64_t)ge.n * ge.ncols;
+    const T* __restrict__ xb = reinterpret_cast<const T*>(ge.x + ge.col0);
+    const T* gb = reinterpret_cast<const T*>(ge.g + ge.col0);  // y_out aliases g: no restrict on the pair
+    T* __restrict__ mb = MOM ? reinterpret_cast<T*>(ge.m + ge.col0) : nullptr;
+    T* yb = reinterpret_cast<T*>(y_out + ge.col0);
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = e / ge.ncols;
+        const int64_t off = row * ldT + (e - row * ge.ncols);
+        const T xv = ld_stream(xb + off);
+        const T gv = ld_stream(gb + off);
+        T mom = gv;
+        if (MOM) {
+            mom = ge.mu * ld_stream(mb + off) + gv;
+            st_stream(mb + off, mom);
+        }
+        yb[off] = half_step<MOM>(xv, gv, mom, ge.lr, ge.mu);  // cached store: pass 2 reads it back
+    }
+}
+
+// Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  Workgroup id = tile * n + i
+// (rows of one column tile are adjacent in launch order).
+template <typename T>
+__global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, float* __restrict__ x_new,
+                                                   int64_t ld, int64_t col0, int64_t ncols, int32_t n,
+                                                   const CsrDev w) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    const int64_t ldT = ld / V;
+    const int64_t tile = blockIdx.x / (unsigned)n;
+    const int i = (int)(blockIdx.x - tile * n);
+    const int64_t col = tile * 256 + threadIdx.x;
+    if (col >= ncols) return;
+    const T* __restrict__ yb = reinterpret_cast<const T*>(y + col0) + col;
+    const int p0 = w.ptr[i], p1 = w.ptr[i + 1];
+    T acc = T(0);
+    for (int p = p0; p < p1; ++p) acc += w.val[p] * yb[(int64_t)w.col[p] * ldT];
+    st_stream(reinterpret_cast<T*>(x_new + col0) + col + (int64_t)i * ldT, acc);
+}
+
+template <typename T>
+hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom) {
+    TileArgs a;
+    a.ge = ge;
+    a.w = w;
+    const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const size_t lds = (size_t)ge.n * kWave * sizeof(T);
+    const dim3 grid((unsigned)tiles), block(kWave * kTileWaves);
+    if (mom == 2) hipLaunchKernelGGL((k_step_tile<T, 2>), grid, block, lds, c->stream, a);
+    else if (mom == 1) hipLaunchKernelGGL((k_step_tile<T, 1>), grid, block, lds, c->stream, a);
+    else hipLaunchKernelGGL((k_step_tile<T, 0>), grid, block, lds, c->stream, a);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom) {
+    float* y = const_cast<float*>(ge.g);  // g is consumed by the step: y takes its place
+    const int64_t total = (int64_t)ge.n * ge.ncols;
+    int64_t blocks = (total + 255) / 256;
+    const int64_t cap = (int64_t)c->num_cus * 32;
+    if (blocks > cap) blocks = cap;
+    if (mom == 2) hipLaunchKernelGGL((k_update_y<T, 2>), dim3((unsigned)blocks), dim3(256), 0, c->stream, ge, y);
+    else if (mom == 1) hipLaunchKernelGGL((k_update_y<T, 1>), dim3((unsigned)blocks), dim3(256), 0, c->stream, ge, y);
+    else hipLaunchKernelGGL((k_update_y<T, 0>), dim3((unsigned)blocks), dim3(256), 0, c->stream, ge, y);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t tiles = (ge.ncols + 255) / 256;
+    if (tiles * ge.n > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((k_spmm_rows<T>), dim3((unsigned)(tiles * ge.n)), dim3(256), 0, c->stream, y, ge.x_new,
+                       ge.ld, ge.col0, ge.ncols, ge.n, w);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec) {
+    if (ge.ncols <= 0) return hipSuccess;
+    if (!c->csr_ready) return hipErrorInvalidValue;
+    const CsrDev w{c->csr_ptr_d, c->csr_col_d, c->csr_val_d};
+    const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
+    const size_t n = (size_t)ge.n;
+    const bool two_pass = c->opt_mix_two_pass == 1;
+    if (vec == 4) {
+        // widest lane type whose n x 64-lane tile fits in LDS (16-byte aligned rows also
+        // satisfy the narrower types)
+        StepGeom g2 = ge;
+        if (!two_pass && n * kWave * sizeof(v4f) <= kTileLdsBytes) return launch_tile<v4f>(c, ge, w, mom);
+        if (!two_pass && n * kWave * sizeof(v2f) <= kTileLdsBytes) {
+            g2.ncols = ge.ncols * 2;
+            return launch_tile<v2f>(c, g2, w, mom);
+        }
+        if (!two_pass && n * kWave * sizeof(float) <= kTileLdsBytes) {
+            g2.ncols = ge.ncols * 4;
+            return launch_tile<float>(c, g2, w, mom);
+        }
+        return launch_two_pass<v4f>(c, ge, w, mom);
+    }
+    if (!two_pass && n * kWave * sizeof(float) <= kTileLdsBytes) return launch_tile<float>(c, ge, w, mom);
+    return launch_two_pass<float>(c, ge, w, mom);
+}

@@ -116,6 +116,17 @@ class Simulation:
     def step(self):
         B.gpga_step(self.ctx)
 
+    def set_mixing(self, W):
+        """Attach a dense (n, n) doubly stochastic W: its non-zeros are handed over in CSR form."""
+        W = np.asarray(W)
+        rows, cols = np.nonzero(W)          # row-major order
+        ptr = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=self.n))])
+        B.gpga_set_mixing_csr(self.ctx, ptr, cols, W[rows, cols].astype(np.float32))
+
+    @property
+    def beta(self) -> float:
+        return B.gpga_mixing_beta(self.ctx)
+
     def set_nesterov(self, on: bool = True):
         B.gpga_set_nesterov(self.ctx, on)
 

@@ -62,7 +62,7 @@ def test_create_rejects_bad_arguments_before_touching_the_device(lib):
     assert call(n=0) == B.GPGA_EINVAL
     assert call(n=-3) == B.GPGA_EINVAL
     assert call(d=0) == B.GPGA_EINVAL
-    assert call(topo=4) == B.GPGA_EINVAL
+    assert call(topo=7) == B.GPGA_EINVAL
     assert call(topo=-1) == B.GPGA_EINVAL
     assert call(H=-1) == B.GPGA_EINVAL
     assert call(lr=float("inf")) == B.GPGA_EINVAL
@@ -111,3 +111,77 @@ def test_input_generators_are_seeded_and_shaped():
     assert yv.shape == (5, 11) and set(np.unique(yv)) <= {-1.0, 1.0}
     cols = inputs.slab_columns(1000, 4, 16)
     assert cols[0] == 0 and cols[-1] == 999 and len(cols) == 64 and (np.diff(cols) > 0).all()
+
+
+# ---- host-side graph logic (no device involved) ---------------------------------------------
+
+def _dense_to_csr(W):
+    import numpy as np
+    rows, cols = np.nonzero(W)
+    ptr = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=W.shape[0]))])
+    return ptr, cols, W[rows, cols].astype(np.float32)
+
+
+def test_topology_beta_reproduces_the_values_printed_in_the_paper(lib):
+    from conftest import read_golden
+    from paper_2105_09080_amd import binding as B
+    for n_s, beta_s in read_golden("ring_beta.txt"):          # Sec. 5.1: ring, n = 20, 50, 100
+        assert abs(B.gpga_topology_beta("ring", int(n_s)) - float(beta_s)) < 1e-3
+
+
+@pytest.mark.parametrize("topology", ["ring", "grid", "expo", "expo1", "none", "full"])
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 20, 50, 64, 100, 300])
+def test_topology_beta_matches_the_oracle(lib, topology, n):
+    from oracle import gpga_oracle as orc
+    from paper_2105_09080_amd import binding as B
+    for k in (0, 1, 5):
+        want = orc.beta_of(orc.mixing_matrix(topology, n, k)) if n > 1 else 0.0
+        # library weights are fp32 (1/3, 1/5, ...): agreement to fp32 rounding of the weights
+        assert B.gpga_topology_beta(topology, n, k) == pytest.approx(want, abs=2e-7)
+
+
+def test_topology_beta_large_sparse_ring(lib):
+    import math
+    from paper_2105_09080_amd import binding as B
+    n = 1024                                                   # 1 - beta = (2/3)(1 - cos(2 pi / n))
+    assert B.gpga_topology_beta("ring", n) == pytest.approx((1 + 2 * math.cos(2 * math.pi / n)) / 3, abs=2e-7)
+    with pytest.raises(B.GpgaError):
+        B.gpga_topology_beta("custom", 8)
+    with pytest.raises(B.GpgaError):
+        B.gpga_topology_beta("ring", 0)
+
+
+def test_check_mixing_csr_accepts_doubly_stochastic_and_rejects_the_rest(lib):
+    import numpy as np
+    from oracle import gpga_oracle as orc
+    from paper_2105_09080_amd import binding as B
+    rng = np.random.default_rng(5)
+    n = 9
+    w = rng.random(4)
+    w /= w.sum()
+    W = w[0] * np.eye(n) + sum(w[t + 1] * np.eye(n)[rng.permutation(n)] for t in range(3))
+    ptr, col, val = _dense_to_csr(W)
+    W32 = np.zeros((n, n))
+    W32[np.repeat(np.arange(n), np.diff(ptr)), col] = val.astype(np.float64)
+    assert B.gpga_check_mixing_csr(n, ptr, col, val) == pytest.approx(orc.beta_of(W32), abs=1e-9)
+
+    def rejected(p, c, v):
+        with pytest.raises(B.GpgaError) as e:
+            B.gpga_check_mixing_csr(n, p, c, v)
+        return e.value.status == B.GPGA_EINVAL
+
+    bad = val.copy(); bad[0] *= 1.01
+    assert rejected(ptr, col, bad)                             # a row sum is off
+    Wr = W.copy(); Wr[[0, 1]] = Wr[[1, 0]]; Wr[0] = W[0]       # row-stochastic only
+    Wr[1] = W[0]
+    assert rejected(*_dense_to_csr(Wr))                        # column sums are off
+    neg = val.copy(); neg[0] = -neg[0]
+    assert rejected(ptr, col, neg)
+    oob = col.copy(); oob[2] = n
+    assert rejected(ptr, oob, val)
+    p2 = ptr.copy(); p2[0] = 1
+    assert rejected(p2, col, val)
+    p3 = ptr.copy(); p3[3], p3[4] = p3[4], p3[3] - 1
+    assert rejected(p3, col, val)
+    nan = val.copy(); nan[1] = float("nan")
+    assert rejected(ptr, col, nan)
