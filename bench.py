@@ -37,13 +37,23 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+def gossip_kernel_name(topology, n):
+    """Which fused kernel runs the gossip steps of this workload."""
+    if topology in ("ring", "expo1", "none"):
+        return "k_step_walk"
+    if topology == "full":
+        return "k_step_global"
+    return "k_step_tile" if n <= 256 else "k_update_y + k_spmm_rows"
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="cfg3", help="primary workload: cfg3 or cfg4 (or cfg5 step-only)")
-    ap.add_argument("--topology", default=None, help="ring or expo1 (default: first listed for the workload)")
+    ap.add_argument("--topology", default=None,
+                    help="ring, expo1, grid, expo, none or full (default: first listed for the workload)")
     ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1",
                     help="comma list of extra workload:topology pairs measured after the primary ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -210,8 +220,8 @@ def main():
         "step_only_steps_per_s": main_res["step_only_steps_per_s"],
         "roofline": {
             "bound": "hbm",
-            "kernel": f"fused {main_res['dominant']} step (k_step_walk)" if main_res["dominant"] == "gossip"
-                      else "fused global-average step (k_step_global)",
+            "kernel": f"fused gossip step ({gossip_kernel_name(topo, main_res['n'])})"
+                      if main_res["dominant"] == "gossip" else "fused global-average step (k_step_global)",
             "achieved": main_res["achieved_gbs"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",

@@ -694,6 +694,14 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "xcd_swizzle")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
         c->opt_xcd_swizzle = (int)value;
+    } else if (!strcmp(name, "mix_lane_bytes")) {
+        if (value != 0 && value != 4 && value != 8 && value != 16)
+            return fail(c, GPGA_EINVAL, "mix_lane_bytes must be 0, 4, 8 or 16");
+        c->opt_mix_lane_bytes = (int)value;
+    } else if (!strcmp(name, "mix_waves")) {
+        if (value != 0 && value != 2 && value != 4 && value != 8 && value != 16)
+            return fail(c, GPGA_EINVAL, "mix_waves must be 0, 2, 4, 8 or 16");
+        c->opt_mix_waves = (int)value;
     } else if (!strcmp(name, "mix_two_pass")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_two_pass must be 0 or 1");
         c->opt_mix_two_pass = (int)value;

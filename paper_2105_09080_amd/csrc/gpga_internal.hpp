@@ -76,6 +76,8 @@ struct gpga_ctx {
     int opt_row_split = 0;
     int opt_row_lanes = 0;
     int opt_xcd_swizzle = 0;
+    int opt_mix_lane_bytes = 0;  // sparse-W tile kernel: widest lane type allowed (0 = automatic, 4, 8, 16)
+    int opt_mix_waves = 0;       // sparse-W tile kernel: wavefronts per workgroup (0 = automatic, 2, 4, 8, 16)
     int opt_mix_two_pass = 0;  // 1 = sparse-W steps always take the two-pass path
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;

@@ -49,18 +49,20 @@ struct TileArgs {
     CsrDev w;
 };
 
-constexpr int kTileWaves = 4;
+constexpr int kTileWavesDefault = 4;
+constexpr int kTileWavesMax = 16;
 constexpr int kTileUnroll = 4;
 constexpr size_t kTileLdsBytes = 64 * 1024;
 
 template <typename T, int MOM>
-__global__ void __launch_bounds__(kWave* kTileWaves) k_step_tile(const TileArgs a) {
+__global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     extern __shared__ __align__(16) unsigned char s_raw[];
     T* __restrict__ sy = reinterpret_cast<T*>(s_raw);  // [n][kWave]
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kTileWaves = blockDim.x >> 6;
     const int n = a.ge.n;
     const int64_t ldT = a.ge.ld / V;
     const float lr = a.ge.lr, mu = a.ge.mu;
@@ -103,13 +105,45 @@ __global__ void __launch_bounds__(kWave* kTileWaves) k_step_tile(const TileArgs 
         }
     }
     __syncthreads();
-    // Phase 2: output rows wave, wave + 4, ... from the staged y.
-    if (!on) return;
+    // Phase 2: output rows wave, wave + 4, ... from the staged y.  The (j, w_ij) list of
+    // a row is fetched with one coalesced load (lane p holds entry p; the next row's list
+    // is fetched while this row is being summed) and broadcast entry by entry with
+    // readlane; taps are taken four at a time (padding taps have weight 0 and read row 0)
+    // so that four LDS reads are in flight.  All lanes stay active: readlane must find
+    // every source lane's registers written.
+    auto fetch_list = [&](int i, int c0, int& cj, float& wv) {
+        cj = 0;
+        wv = 0.f;
+        if (i < n) {
+            const int p = a.w.ptr[i] + c0 + lane;
+            if (p < a.w.ptr[i + 1]) {
+                cj = a.w.col[p];
+                wv = a.w.val[p];
+            }
+        }
+    };
+    int cj_next;
+    float wv_next;
+    fetch_list(wave, 0, cj_next, wv_next);
     for (int i = wave; i < n; i += kTileWaves) {
-        const int p0 = a.w.ptr[i], p1 = a.w.ptr[i + 1];
+        const int cnt = a.w.ptr[i + 1] - a.w.ptr[i];
+        int cj_l = cj_next;
+        float wv_l = wv_next;
+        fetch_list(i + kTileWaves, 0, cj_next, wv_next);
         T acc = T(0);
-        for (int p = p0; p < p1; ++p) acc += a.w.val[p] * sy[a.w.col[p] * kWave + lane];
-        st_stream(xnp + (int64_t)i * ldT, acc);
+        for (int c0 = 0; c0 < cnt; c0 += kWave) {
+            if (c0 > 0) fetch_list(i, c0, cj_l, wv_l);
+            const int m = cnt - c0 < kWave ? cnt - c0 : kWave;
+            for (int q = 0; q < m; q += 4) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int cj = __builtin_amdgcn_readlane(cj_l, q + t);
+                    const float wv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wv_l), q + t));
+                    acc += wv * sy[cj * kWave + lane];
+                }
+            }
+        }
+        if (on) st_stream(xnp + (int64_t)i * ldT, acc);
     }
 }
 
@@ -165,7 +199,10 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
     if (tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t lds = (size_t)ge.n * kWave * sizeof(T);
-    const dim3 grid((unsigned)tiles), block(kWave * kTileWaves);
+    // measured on the n = 64, d = 25.6M shape: 8 or 16 wavefronts per workgroup stream
+    // 5.2-6.0 TB/s, 4 wavefronts 4.8-5.1 TB/s (more rows are in flight while others mix)
+    const int waves = c->opt_mix_waves ? c->opt_mix_waves : (ge.n >= 32 ? 8 : kTileWavesDefault);
+    const dim3 grid((unsigned)tiles), block(kWave * waves);
     if (mom == 2) hipLaunchKernelGGL((k_step_tile<T, 2>), grid, block, lds, c->stream, a);
     else if (mom == 1) hipLaunchKernelGGL((k_step_tile<T, 1>), grid, block, lds, c->stream, a);
     else hipLaunchKernelGGL((k_step_tile<T, 0>), grid, block, lds, c->stream, a);
@@ -200,12 +237,14 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec) {
     const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     const size_t n = (size_t)ge.n;
     const bool two_pass = c->opt_mix_two_pass == 1;
+    const size_t lane_cap = c->opt_mix_lane_bytes ? (size_t)c->opt_mix_lane_bytes : 16;
     if (vec == 4) {
         // widest lane type whose n x 64-lane tile fits in LDS (16-byte aligned rows also
         // satisfy the narrower types)
         StepGeom g2 = ge;
-        if (!two_pass && n * kWave * sizeof(v4f) <= kTileLdsBytes) return launch_tile<v4f>(c, ge, w, mom);
-        if (!two_pass && n * kWave * sizeof(v2f) <= kTileLdsBytes) {
+        if (!two_pass && lane_cap >= 16 && n * kWave * sizeof(v4f) <= kTileLdsBytes)
+            return launch_tile<v4f>(c, ge, w, mom);
+        if (!two_pass && lane_cap >= 8 && n * kWave * sizeof(v2f) <= kTileLdsBytes) {
             g2.ncols = ge.ncols * 2;
             return launch_tile<v2f>(c, g2, w, mom);
         }
