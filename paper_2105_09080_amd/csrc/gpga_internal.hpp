@@ -21,7 +21,8 @@ enum GpgaProblem : int { PROB_NONE = 0, PROB_LSQ, PROB_LOGREG, PROB_LOGREG_VIRTU
 enum StencilMode : int {
     MODE_RING = 0,  // (prev + cur + next) / 3
     MODE_PEER = 1,  // (cur + next) / 2
-    MODE_SELF = 2   // cur
+    MODE_SELF = 2,  // cur
+    MODE_INPLACE = 3  // cur, stored over the gradient it was computed from (x_new untouched)
 };
 
 // A sparse mixing matrix W in compressed-row form: row i lists the nodes j whose

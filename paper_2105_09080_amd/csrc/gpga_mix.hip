@@ -14,7 +14,8 @@
 //    element of x, m, g is read from HBM once and m, x_new written once (20 B per
 //    element), exactly like the ring / one-peer stencil kernels.
 //  * two-pass path (more rows than LDS can hold): pass 1 is the elementwise local
-//    update, which overwrites g with y (g is consumed by the step anyway);
+//    update (the W = I walk of the stencil kernel), which overwrites g with y
+//    (g is consumed by the step anyway);
 //    pass 2 is the sparse product x_new = W y with workgroups ordered so that
 //    all rows of a column tile run together and re-reads of y hit the caches
 //    (28 B per element of HBM traffic when they do).
@@ -147,41 +148,30 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
     }
 }
 
-// Two-pass path, pass 1: m <- mu m + g, y = x^(k+1/2) written over g.
-template <typename T, int MOM>
-__global__ void __launch_bounds__(256) k_update_y(const StepGeom ge, float* y_out) {
-    constexpr int V = sizeof(T) / sizeof(float);
-    const int64_t ldT = ge.ld / V;
-    const int64_t total = (int64_t)ge.n * ge.ncols;
-    const T* __restrict__ xb = reinterpret_cast<const T*>(ge.x + ge.col0);
-    const T* gb = reinterpret_cast<const T*>(ge.g + ge.col0);  // y_out aliases g: no restrict on the pair
-    T* __restrict__ mb = MOM ? reinterpret_cast<T*>(ge.m + ge.col0) : nullptr;
-    T* yb = reinterpret_cast<T*>(y_out + ge.col0);
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-         e += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = e / ge.ncols;
-        const int64_t off = row * ldT + (e - row * ge.ncols);
-        const T xv = ld_stream(xb + off);
-        const T gv = ld_stream(gb + off);
-        T mom = gv;
-        if (MOM) {
-            mom = ge.mu * ld_stream(mb + off) + gv;
-            st_stream(mb + off, mom);
-        }
-        yb[off] = half_step<MOM>(xv, gv, mom, ge.lr, ge.mu);  // cached store: pass 2 reads it back
-    }
-}
-
-// Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  Workgroup id = tile * n + i
-// (rows of one column tile are adjacent in launch order).
+// Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  One workgroup = one row of one
+// column tile (256 lanes).  Workgroup ids are dealt to the 8 XCDs round-robin, each
+// with its own L2; the id is remapped so that all rows of a tile run on ONE XCD, in
+// row order: the y rows a tile needs are then fetched into that L2 once and re-read
+// from it by the neighbouring rows.
 template <typename T>
 __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, float* __restrict__ x_new,
                                                    int64_t ld, int64_t col0, int64_t ncols, int32_t n,
-                                                   const CsrDev w) {
+                                                   int64_t tiles, const CsrDev w) {
     constexpr int V = sizeof(T) / sizeof(float);
     const int64_t ldT = ld / V;
-    const int64_t tile = blockIdx.x / (unsigned)n;
-    const int i = (int)(blockIdx.x - tile * n);
+    const int64_t bid = blockIdx.x;
+    const int64_t full = (tiles >> 3) << 3;          // tiles covered by whole groups of 8
+    int64_t tile;
+    int i;
+    if (bid < full * n) {
+        const int64_t slot = bid >> 3;               // position within this XCD's queue
+        tile = (slot / n) * 8 + (bid & 7);
+        i = (int)(slot % n);
+    } else {                                         // ragged tail: plain order
+        const int64_t r = bid - full * n;
+        tile = full + r / n;
+        i = (int)(r % n);
+    }
     const int64_t col = tile * 256 + threadIdx.x;
     if (col >= ncols) return;
     const T* __restrict__ yb = reinterpret_cast<const T*>(y + col0) + col;
@@ -210,21 +200,14 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
 }
 
 template <typename T>
-hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom) {
-    float* y = const_cast<float*>(ge.g);  // g is consumed by the step: y takes its place
-    const int64_t total = (int64_t)ge.n * ge.ncols;
-    int64_t blocks = (total + 255) / 256;
-    const int64_t cap = (int64_t)c->num_cus * 32;
-    if (blocks > cap) blocks = cap;
-    if (mom == 2) hipLaunchKernelGGL((k_update_y<T, 2>), dim3((unsigned)blocks), dim3(256), 0, c->stream, ge, y);
-    else if (mom == 1) hipLaunchKernelGGL((k_update_y<T, 1>), dim3((unsigned)blocks), dim3(256), 0, c->stream, ge, y);
-    else hipLaunchKernelGGL((k_update_y<T, 0>), dim3((unsigned)blocks), dim3(256), 0, c->stream, ge, y);
-    hipError_t e = hipGetLastError();
+hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int vec) {
+    // pass 1: the W = I walk of the stencil kernel, storing y = x^(k+1/2) over g
+    hipError_t e = launch_step_walk(c, ge, MODE_INPLACE, 0, vec);
     if (e != hipSuccess) return e;
     const int64_t tiles = (ge.ncols + 255) / 256;
     if (tiles * ge.n > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((k_spmm_rows<T>), dim3((unsigned)(tiles * ge.n)), dim3(256), 0, c->stream, y, ge.x_new,
-                       ge.ld, ge.col0, ge.ncols, ge.n, w);
+    hipLaunchKernelGGL((k_spmm_rows<T>), dim3((unsigned)(tiles * ge.n)), dim3(256), 0, c->stream, ge.g, ge.x_new,
+                       ge.ld, ge.col0, ge.ncols, ge.n, tiles, w);
     return hipGetLastError();
 }
 
@@ -252,8 +235,8 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec) {
             g2.ncols = ge.ncols * 4;
             return launch_tile<float>(c, g2, w, mom);
         }
-        return launch_two_pass<v4f>(c, ge, w, mom);
+        return launch_two_pass<v4f>(c, ge, w, 4);
     }
     if (!two_pass && n * kWave * sizeof(float) <= kTileLdsBytes) return launch_tile<float>(c, ge, w, mom);
-    return launch_two_pass<float>(c, ge, w, mom);
+    return launch_two_pass<float>(c, ge, w, 1);
 }

@@ -16,7 +16,8 @@
 // permutation i -> (i + S) mod n:
 //   ring      S = 1      one cycle of length n, taps (prev, cur, next)/3
 //   one-peer  S = 2^s    gcd(S,n) cycles of length n/gcd, taps (cur, next)/2
-//   W = I     -          n cycles of length 1, tap cur
+//   W = I     -          n cycles of length 1, tap cur (also used, writing y over g,
+//                        as the first pass of sparse-W steps with many rows)
 // A "walker" is one wavefront walking a contiguous segment of one cycle with
 // the last two y values kept in registers.  When a cycle is split over Q
 // wavefronts of a workgroup (few columns, many rows) the first/last y of every
@@ -251,12 +252,15 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 if (len >= 2) load_row(x1, m1, g1, r1);
                 yf = y_of(x0, m0, g0, r0);
                 if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r0 * ldT, yf);
+                // in place: through a pointer derived from gp, the one this element was read with
+                if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(gp) + (int64_t)r0 * ldT, yf);
                 pc = yf;
                 row_prev = r0;
                 if (len >= 2) {
                     ys = y_of(x1, m1, g1, r1);
                     if (MODE == MODE_PEER) st_stream(xnp + (int64_t)r0 * ldT, (yf + ys) * 0.5f);
                     if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r1 * ldT, ys);
+                    if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(gp) + (int64_t)r1 * ldT, ys);
                     pp = yf;
                     pc = ys;
                     row_prev = r1;
@@ -302,7 +306,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 emit(y_of(xv, mv, gv, rw), rw);
             }
         }
-        if (MODE == MODE_SELF) continue;
+        if (MODE == MODE_SELF || MODE == MODE_INPLACE) continue;
 
         // Close the stencil at the two ends of the segment.  One walker per
         // cycle: the cycle closes on itself.  Q walkers per cycle: neighbours'
@@ -592,6 +596,7 @@ hipError_t launch_walk_mode(int mode, int U, const LaunchPlan& plan, hipStream_t
     switch (mode) {
         case MODE_RING: return launch_walk_u<T, MODE_RING, MOM>(U, plan, st, a);
         case MODE_PEER: return launch_walk_u<T, MODE_PEER, MOM>(U, plan, st, a);
+        case MODE_INPLACE: return launch_walk_u<T, MODE_INPLACE, MOM>(U, plan, st, a);
         default: return launch_walk_u<T, MODE_SELF, MOM>(U, plan, st, a);
     }
 }
@@ -641,7 +646,7 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const int n = ge.n;
     WalkArgs a;
     a.ge = ge;
-    if (mode == MODE_SELF) {
+    if (mode == MODE_SELF || mode == MODE_INPLACE) {
         a.S = 0;
         a.C = n;
         a.L = 1;
@@ -654,7 +659,7 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
 
     int Q = 1;
-    if (mode != MODE_SELF) {
+    if (mode != MODE_SELF && mode != MODE_INPLACE) {
         if (c->opt_row_split) {
             Q = c->opt_row_split;
         } else if (tiles * a.C < kPacedWaves) {
