@@ -61,11 +61,14 @@ def parse_args():
                     help="run this many plain device copies of one n x d buffer before the timed loop "
                          "(a kernel of known size: reads and writes 4*n*d bytes; used to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--trace", type=int, default=-1,
+                    help="1 = record the consensus distance after every step on the device (gpga_set_trace), "
+                         "0 = do not; default: on for cfg5 (which reports it), off otherwise")
     ap.add_argument("--opt", action="append", default=[], help="launch option name=value (repeatable)")
     return ap.parse_args()
 
 
-def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0):
+def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1):
     """Times `steps` passes of local_grad + step.  Returns a dict of measurements."""
     import torch
 
@@ -87,6 +90,8 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0):
         idx = sim.upload_batches(inputs.batch_indices(steps + warmup, n, c["B"], c["M"], c["seed"]))
         grad = lambda: sim.local_grad(idx[sim.k])
 
+    want_trace = (cfg_name == "cfg5") if trace < 0 else bool(trace)
+    trace_dev = sim.attach_trace(steps + warmup) if want_trace else None
     with torch.cuda.stream(stream):
         for _ in range(copy_probe):
             sim._bufs[1].copy_(sim._bufs[0])
@@ -133,6 +138,10 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0):
     res["grad_write_gbs"] = 4 * elts / (res["grad_ms_avg"] * 1e-3) / 1e9
     res["step_only_steps_per_s"] = 1e3 / res["step_ms_avg"]
     res["consensus_error_final"] = sim.consensus_error()
+    if trace_dev is not None:
+        tr = trace_dev.cpu().numpy()
+        res["consensus_trace"] = {"steps": int(len(tr)), "first": [float(v) for v in tr[:10]],
+                                  "last": float(tr[-1]), "max": float(tr.max())}
     sim.close()
     del sim
     torch.cuda.empty_cache()
@@ -192,14 +201,14 @@ def main():
         opts[name] = int(v)
 
     topo = args.topology or inputs.CONFIGS[args.config]["topologies"][0]
-    main_res = run_workload(args.config, topo, args.steps, args.warmup, opts, args.copy_probe)
+    main_res = run_workload(args.config, topo, args.steps, args.warmup, opts, args.copy_probe, args.trace)
     others = []
     for item in [s for s in args.also.split(",") if s]:
         name, tp = item.split(":")
         if (name, tp) == (args.config, topo):
             continue
         steps = min(args.steps, inputs.CONFIGS[name]["T"])
-        others.append(run_workload(name, tp, steps, args.warmup, opts))
+        others.append(run_workload(name, tp, steps, args.warmup, opts, trace=args.trace))
 
     out = {
         "metric": "Gossip-PGA steps/s and achieved HBM GB/s (% of peak) for fused n x d step",
@@ -232,6 +241,7 @@ def main():
             "global_step_avg_ms": main_res["global_ms_avg"],
             "global_step_gbs": main_res.get("global_gbs"),
         },
+        "consensus_trace": main_res.get("consensus_trace"),
         "breakdown": {"grad_ms_avg": main_res["grad_ms_avg"], "step_ms_avg": main_res["step_ms_avg"],
                       "grad_write_gbs": main_res["grad_write_gbs"],
                       "n_gossip": main_res["n_gossip"], "n_global": main_res["n_global"]},
@@ -239,7 +249,7 @@ def main():
             {"workload": r["workload"], "steps_per_s": r["steps_per_s"], "step_only_steps_per_s": r["step_only_steps_per_s"],
              "ms_per_step": r["ms_per_step"], "gossip_ms_avg": r["gossip_ms_avg"], "global_ms_avg": r["global_ms_avg"],
              "grad_ms_avg": r["grad_ms_avg"], "achieved_gbs": r["achieved_gbs"], "frac": r["achieved_gbs"] / HBM_PEAK_GBS,
-             "global_step_gbs": r.get("global_gbs")} for r in others],
+             "global_step_gbs": r.get("global_gbs"), "consensus_trace": r.get("consensus_trace")} for r in others],
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, topo)

@@ -268,7 +268,7 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
         c->clock_hz = 1e3 * (double)khz;
     const size_t need = consensus_partials_needed(c);
     if (hipMalloc(reinterpret_cast<void**>(&c->partials), need * sizeof(double)) != hipSuccess) {
-        delete c;
+        (void)gpga_destroy(c);
         return GPGA_ENOMEM;
     }
     c->partials_cap = need;
@@ -276,12 +276,12 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
         (void)hipMemset(c->pace_slots, 0, 64 * sizeof(unsigned long long));
         (void)hipDeviceSynchronize();
     } else {
-        c->pace_slots = nullptr;
+        c->pace_slots = nullptr;  // launches simply run unpaced
     }
     if (hipHostMalloc(reinterpret_cast<void**>(&c->host_scalar), sizeof(double), hipHostMallocDefault) !=
         hipSuccess) {
-        (void)hipFree(c->partials);
-        delete c;
+        c->host_scalar = nullptr;
+        (void)gpga_destroy(c);
         return GPGA_ENOMEM;
     }
     if (topology == GPGA_TOPO_GRID || topology == GPGA_TOPO_EXPO) {
@@ -509,20 +509,55 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
     ge.mu = c->mu;
     const int64_t nv = vec ? c->d / 4 : 0;
     const int64_t tail = c->d - nv * 4;
+    // Consensus trace of this iteration: 0 after a global average (all rows get the same
+    // bits); sums produced by the fused kernel itself when it stores whole columns in
+    // one vector pass; else one reduction pass over the new X.  Nothing here waits.
+    const bool trace = c->trace && c->k < c->trace_cap;
+    int64_t spread_count = 0;
     hipError_t e = hipSuccess;
     for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {
         ge.col0 = pass == 0 ? 0 : nv * 4;
         ge.ncols = pass == 0 ? nv : tail;
         if (ge.ncols == 0) continue;
         const int v = pass == 0 ? 4 : 1;
+        const bool fuse = trace && !global && !csr && tail == 0;
         e = global ? launch_step_global(c, ge, v)
-                   : csr ? launch_step_csr(c, ge, v) : launch_step_walk(c, ge, mode, S, v);
+                   : csr ? launch_step_csr(c, ge, v)
+                         : launch_step_walk(c, ge, mode, S, v, fuse ? c->partials + 1 : nullptr,
+                                            fuse ? &spread_count : nullptr);
     }
     if (e != hipSuccess) return hip_fail(c, e, "step kernel launch");
     float* t = c->x;
     c->x = c->x_new;
     c->x_new = t;
+    if (trace) {
+        double* slot = c->trace + c->k;
+        if (global) {
+            e = launch_trace_store(c, c->partials, 0, slot);
+        } else if (spread_count > 0) {
+            e = launch_trace_store(c, c->partials + 1, spread_count, slot);
+        } else {
+            size_t need = 0;
+            e = launch_consensus_sq(c, &need);  // sum of squares of the live (new) X into partials[0]
+            if (e == hipSuccess) e = launch_trace_store(c, c->partials, 1, slot);
+        }
+        if (e != hipSuccess) return hip_fail(c, e, "consensus trace launch");
+    }
     c->k += 1;
+    return GPGA_OK;
+}
+
+gpga_status gpga_set_trace(gpga_ctx* c, double* trace_dev, int64_t capacity) {
+    if (!c) return GPGA_EINVAL;
+    if (trace_dev && (!aligned(trace_dev, 8) || capacity < 1))
+        return fail(c, GPGA_EINVAL, "trace_dev must be 8-byte aligned with capacity >= 1");
+    if (trace_dev) {
+        DeviceGuard guard(c->device);
+        const gpga_status s = grow_f64(c, &c->partials, &c->partials_cap, consensus_partials_needed(c));
+        if (s != GPGA_OK) return s;
+    }
+    c->trace = trace_dev;
+    c->trace_cap = trace_dev ? capacity : 0;
     return GPGA_OK;
 }
 
@@ -708,6 +743,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "pace_gbs")) {
         if (value < -1 || value > 16000) return fail(c, GPGA_EINVAL, "pace_gbs must be -1 (automatic), 0 (off) or a rate up to 16000 GB/s");
         c->opt_pace_gbs = (int)value;
+    } else if (!strcmp(name, "pace_min_cycle")) {
+        if (value < 0 || value > (1 << 24)) return fail(c, GPGA_EINVAL, "pace_min_cycle must be 0 (automatic) or a row count");
+        c->opt_pace_min_cycle = (int)value;
     } else if (!strcmp(name, "blocks_per_cu")) {
         if (value < -1 || value > 32) return fail(c, GPGA_EINVAL, "blocks_per_cu must be -1 (automatic), 0 (off) or 1..32");
         c->opt_blocks_per_cu = (int)value;

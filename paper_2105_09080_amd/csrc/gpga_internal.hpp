@@ -83,6 +83,7 @@ struct gpga_ctx {
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
     int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
+    int opt_pace_min_cycle = 0;  // shortest row cycle that is paced (0 = automatic)
     uint32_t pace_seq = 0;   // sequence number of paced launches
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
     unsigned long long* pace_slots = nullptr;  // 64 device words, library-owned
@@ -100,6 +101,10 @@ struct gpga_ctx {
     int64_t sched_period = 1, sched_warmup = 0, sched_total = 0;
     int sched_count = 0;
     int64_t sched_milestones[kMaxMilestones] = {0};
+
+    // consensus trace (borrowed device array)
+    double* trace = nullptr;
+    int64_t trace_cap = 0;
 
     // adaptive averaging period (Algorithm 2)
     bool aga = false;
@@ -125,7 +130,11 @@ struct StepGeom {
 // ---- launchers (each returns hipSuccess or the launch error) ----------------
 
 // Gossip step: stencil `mode` along cycles of the row permutation i -> (i+S) mod n.
-hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec);
+// If spread_partials / spread_count are given and one walker stores whole columns, the
+// kernel also writes one partial sum of squared deviations from the column means of
+// x_new per workgroup and *spread_count receives their number (0 = not produced).
+hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec,
+                            double* spread_partials = nullptr, int64_t* spread_count = nullptr);
 // Global-average step.
 hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec);
 
@@ -157,5 +166,7 @@ hipError_t launch_col_mean(const gpga_ctx* c, float* xbar);
 // Sum of squared deviations into c->partials[0] (device double).
 hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed);
 size_t consensus_partials_needed(const gpga_ctx* c);
+// slot[0] = sqrt(sum of `count` partials) (count = 0 stores 0): one entry of the consensus trace.
+hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot);
 // out[0] = mean of count floats (one workgroup, fp64 accumulation).
 hipError_t launch_mean_f32(const gpga_ctx* c, const float* v, int64_t count, double* out);

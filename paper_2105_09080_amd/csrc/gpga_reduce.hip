@@ -148,6 +148,19 @@ __global__ void __launch_bounds__(256) k_final_sum(const double* __restrict__ pa
     if (threadIdx.x == 0) out[0] = (s_buf[0] + s_buf[1]) + (s_buf[2] + s_buf[3]);
 }
 
+// slot[0] = sqrt(sum of `count` partials), one workgroup, fixed order.
+__global__ void __launch_bounds__(256) k_trace_store(const double* __restrict__ partials, int64_t count,
+                                                     double* __restrict__ slot) {
+    __shared__ double s_buf[4];
+    double acc = 0.0;
+    for (int64_t t = threadIdx.x; t < count; t += blockDim.x) acc += partials[t];
+    acc = wave_sum(acc);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) s_buf[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) slot[0] = sqrt((s_buf[0] + s_buf[1]) + (s_buf[2] + s_buf[3]));
+}
+
 // out[0] = (1/count) sum v[i], one workgroup, fixed order.
 __global__ void __launch_bounds__(256) k_mean_f32(const float* __restrict__ v, int64_t count,
                                                   double* __restrict__ out) {
@@ -230,6 +243,11 @@ hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
                            c->ld, nv * 4, tail, c->n, parts + b1);
     }
     hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(256), 0, c->stream, parts, b1 + b2, c->partials);
+    return hipGetLastError();
+}
+
+hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot) {
+    hipLaunchKernelGGL(k_trace_store, dim3(1), dim3(256), 0, c->stream, partials, count, slot);
     return hipGetLastError();
 }
 

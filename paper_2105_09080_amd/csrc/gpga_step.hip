@@ -71,6 +71,48 @@ __device__ __forceinline__ T half_step(const T& xv, const T& gv, const T& mom, f
     return xv - lr * mom;
 }
 
+// Running consensus sums of the values a lane stores into its column group of
+// x_new (all n rows of it): shifted by a reference close to them (the old iterate of
+// the first row, set by the caller before the first add), deviations
+// formed in fp32 (exact or nearly so while rows are close), sums in fp64, so
+// that sum_i (x_i - xbar)^2 = S2 - S1^2 / n keeps the small quantity.
+template <typename T>
+struct ColumnSpread;
+template <>
+struct ColumnSpread<v4f> {
+    v4f ref;
+    double s1[4], s2[4];
+    __device__ __forceinline__ void reset(const v4f& r) {
+        ref = r;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s1[j] = s2[j] = 0.0;
+    }
+    __device__ __forceinline__ void add(const v4f& v) {  // branch-free: it sits in the pipelined loop
+        const v4f dl = v - ref;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double t = (double)dl[j];
+            s1[j] += t;
+            s2[j] += t * t;
+        }
+    }
+    __device__ __forceinline__ double sum_sq(double inv_n) const {
+        double r = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double v = s2[j] - s1[j] * s1[j] * inv_n;
+            r += v > 0.0 ? v : 0.0;
+        }
+        return r;
+    }
+};
+template <>
+struct ColumnSpread<float> {  // never instantiated with tracing on; keeps the template uniform
+    __device__ __forceinline__ void reset(float) {}
+    __device__ __forceinline__ void add(float) {}
+    __device__ __forceinline__ double sum_sq(double) const { return 0.0; }
+};
+
 constexpr int kMaxWaves = 8;
 constexpr int kDefaultUnroll = 2;  // rows per batch; two batches are in flight (software pipeline)
 
@@ -91,6 +133,7 @@ struct WalkArgs {
     int32_t xcd;  // remap tile groups so that an XCD sees contiguous tiles
     int64_t gx;   // tile groups
     int64_t gy;   // walker groups; work items = gx * gy, tile group fastest
+    double* spread_partials;  // TRACE kernels: one sum of squared deviations per workgroup
     PaceArgs pace;
 };
 
@@ -144,11 +187,16 @@ __device__ __forceinline__ void pace_wait(const PaceArgs& p, unsigned long long 
 }
 
 // MOM: 0 = no momentum buffer, 1 = heavy-ball, 2 = Nesterov.
-template <typename T, int MODE, int MOM, int U>
+// TRACE: also sum (x_new - column mean)^2 over everything stored; requires that one
+// walker covers whole columns (one cycle, one segment), which the launcher checks.
+template <typename T, int MODE, int MOM, int U, bool TRACE = false>
 __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     __shared__ T s_first[kMaxWaves][kWave];
     __shared__ T s_last[kMaxWaves][kWave];
+    __shared__ double s_spread[kMaxWaves];
+    ColumnSpread<T> spread;
+    double spread_acc = 0.0;
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform -> SGPR
@@ -194,6 +242,10 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
         const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + coff;
         T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + coff : nullptr;
         T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + coff;
+        auto put = [&](int rw, const T& v) {
+            st_stream(xnp + (int64_t)rw * ldT, v);
+            if (TRACE) spread.add(v);
+        };
 
         T yf = T(0), ys = T(0), pp = T(0), pc = T(0);
         int row = row_first;
@@ -220,8 +272,8 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
         // Steady state (third row of the segment onwards): the new y completes the
         // stencil of the previous row.
         auto emit = [&](const T& y, int rw) {
-            if (MODE == MODE_RING) st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + y) * third);
-            if (MODE == MODE_PEER) st_stream(xnp + (int64_t)row_prev * ldT, (pc + y) * 0.5f);
+            if (MODE == MODE_RING) put(row_prev, (pp + pc + y) * third);
+            if (MODE == MODE_PEER) put(row_prev, (pc + y) * 0.5f);
             pp = pc;
             pc = y;
             row_prev = rw;
@@ -250,6 +302,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 units_done += (len >= 2 ? 2u : 1u) * kRowUnits;
                 load_row(x0, m0, g0, r0);
                 if (len >= 2) load_row(x1, m1, g1, r1);
+                if (TRACE) spread.reset(x0);
                 yf = y_of(x0, m0, g0, r0);
                 if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r0 * ldT, yf);
                 // in place: through a pointer derived from gp, the one this element was read with
@@ -258,7 +311,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 row_prev = r0;
                 if (len >= 2) {
                     ys = y_of(x1, m1, g1, r1);
-                    if (MODE == MODE_PEER) st_stream(xnp + (int64_t)r0 * ldT, (yf + ys) * 0.5f);
+                    if (MODE == MODE_PEER) put(r0, (yf + ys) * 0.5f);
                     if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r1 * ldT, ys);
                     if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(gp) + (int64_t)r1 * ldT, ys);
                     pp = yf;
@@ -324,14 +377,28 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
         if (on) {
             if (MODE == MODE_RING) {
                 if (len == 1) {
-                    st_stream(xnp + (int64_t)row_first * ldT, (left + yf + right) * third);
+                    put(row_first, (left + yf + right) * third);
                 } else {
-                    st_stream(xnp + (int64_t)row_first * ldT, (left + yf + ys) * third);
-                    st_stream(xnp + (int64_t)row_prev * ldT, (pp + pc + right) * third);
+                    put(row_first, (left + yf + ys) * third);
+                    put(row_prev, (pp + pc + right) * third);
                 }
             } else {  // MODE_PEER: last row of the segment pairs with the next segment's first
-                st_stream(xnp + (int64_t)row_prev * ldT, (pc + right) * 0.5f);
+                put(row_prev, (pc + right) * 0.5f);
             }
+            if (TRACE) spread_acc += spread.sum_sq(1.0 / (double)n);
+        }
+    }
+    if (TRACE) {
+        // one partial per workgroup, summed in a fixed order
+        double v = spread_acc;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+        if (lane == 0) s_spread[wave] = v;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int w = 0; w < waves; ++w) t += s_spread[w];
+            a.spread_partials[blockIdx.x] = t;
         }
     }
 }
@@ -547,6 +614,7 @@ struct LaunchPlan {
     double clock_hz = 1e8;
     int vec = 4;
     const gpga_ctx* ctx = nullptr;
+    int64_t* blocks_out = nullptr;  // receives the number of workgroups launched
 };
 
 template <typename Args, typename Kernel>
@@ -577,6 +645,7 @@ hipError_t launch_planned(Kernel kernel, LaunchPlan plan, Args a, hipStream_t st
         }
     }
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    if (plan.blocks_out) *plan.blocks_out = blocks;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(threads), 0, st, a);
     return hipGetLastError();
 }
@@ -589,6 +658,17 @@ hipError_t launch_walk_u(int U, const LaunchPlan& plan, hipStream_t st, const Wa
         case 8: return launch_planned(k_step_walk<T, MODE, MOM, 8>, plan, a, st);
         default: return launch_planned(k_step_walk<T, MODE, MOM, 4>, plan, a, st);
     }
+}
+
+// Tracing variants exist for the default geometry only (128-bit lanes, 1 or 2 rows per batch).
+template <int MOM>
+hipError_t launch_walk_trace(int mode, int U, const LaunchPlan& plan, hipStream_t st, const WalkArgs& a) {
+    if (mode == MODE_RING) {
+        return U == 1 ? launch_planned(k_step_walk<v4f, MODE_RING, MOM, 1, true>, plan, a, st)
+                      : launch_planned(k_step_walk<v4f, MODE_RING, MOM, 2, true>, plan, a, st);
+    }
+    return U == 1 ? launch_planned(k_step_walk<v4f, MODE_PEER, MOM, 1, true>, plan, a, st)
+                  : launch_planned(k_step_walk<v4f, MODE_PEER, MOM, 2, true>, plan, a, st);
 }
 
 template <typename T, int MOM>
@@ -621,6 +701,7 @@ constexpr int64_t kPacedWaves = 2048;
 // persistent and paced; everything else is a one-shot launch.
 constexpr int kAutoBlocksPerCu = 4;
 constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
+constexpr double kAutoPaceGbsShort = 6000.0;   // walks over cycles of 8 rows
 constexpr double kAutoPaceGbsGlobal = 5950.0;  // the global-average kernel saturates a little lower
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
@@ -641,7 +722,9 @@ LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool w
 
 }  // namespace
 
-hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec) {
+hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int32_t S, int vec,
+                            double* spread_partials, int64_t* spread_count) {
+    if (spread_count) *spread_count = 0;
     if (ge.ncols <= 0) return hipSuccess;
     const int n = ge.n;
     WalkArgs a;
@@ -689,10 +772,24 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     // pacing assumes every wavefront does the same work: one walker per cycle, equal segments
     const bool uniform = (Q == 1) && (((int64_t)a.C * Q) % wpb == 0);
     // short cycles (< 8 rows per wavefront) already keep few rows open in a one-shot launch
-    const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= 8, kAutoPaceGbsWalk);
+    const int min_cycle = c->opt_pace_min_cycle > 0 ? c->opt_pace_min_cycle : 8;
+    // cycles of exactly 8 rows (one-peer offset n/8) peak at a slightly lower target: 5.98 TB/s
+    // at 6.0 against 5.68 TB/s at 6.3 on the n = 64, d = 25.6M shape
+    const double auto_gbs = a.L <= 8 ? kAutoPaceGbsShort : kAutoPaceGbsWalk;
+    const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= min_cycle, auto_gbs);
     // paced wavefronts advance one row per batch (two rows in flight); free-running ones two
     const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : kDefaultUnroll);
     const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
+    a.spread_partials = nullptr;
+    // the consensus sums can ride along when one walker stores whole columns
+    if (spread_partials && spread_count && vec == 4 && Q == 1 && a.C == 1 && (U == 1 || U == 2) &&
+        (mode == MODE_RING || mode == MODE_PEER)) {
+        LaunchPlan tp = plan;
+        tp.blocks_out = spread_count;
+        a.spread_partials = spread_partials;
+        if (mom == 2) return launch_walk_trace<2>(mode, U, tp, c->stream, a);
+        return mom ? launch_walk_trace<1>(mode, U, tp, c->stream, a) : launch_walk_trace<0>(mode, U, tp, c->stream, a);
+    }
     if (vec == 4) {
         if (mom == 2) return launch_walk_mode<v4f, 2>(mode, U, plan, c->stream, a);
         return mom ? launch_walk_mode<v4f, 1>(mode, U, plan, c->stream, a)

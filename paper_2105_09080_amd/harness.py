@@ -148,6 +148,13 @@ class Simulation:
     def consensus_error(self) -> float:
         return B.gpga_consensus_error(self.ctx)
 
+    def attach_trace(self, capacity: int) -> torch.Tensor:
+        """Device array that receives the consensus distance after every step (no host sync)."""
+        self.trace = torch.full((capacity,), float("nan"), dtype=torch.float64, device=self.device)
+        self.stream.synchronize()
+        B.gpga_set_trace(self.ctx, self.trace, capacity)
+        return self.trace
+
     def mean(self) -> torch.Tensor:
         out = torch.empty(self.d, dtype=torch.float32, device=self.device)
         B.gpga_mean(self.ctx, out)
