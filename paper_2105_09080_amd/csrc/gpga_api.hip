@@ -537,9 +537,7 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
         } else if (spread_count > 0) {
             e = launch_trace_store(c, c->partials + 1, spread_count, slot);
         } else {
-            size_t need = 0;
-            e = launch_consensus_sq(c, &need);  // sum of squares of the live (new) X into partials[0]
-            if (e == hipSuccess) e = launch_trace_store(c, c->partials, 1, slot);
+            e = launch_consensus_trace(c, slot);  // reduction pass over the live (new) X
         }
         if (e != hipSuccess) return hip_fail(c, e, "consensus trace launch");
     }

@@ -166,6 +166,8 @@ hipError_t launch_col_mean(const gpga_ctx* c, float* xbar);
 // Sum of squared deviations into c->partials[0] (device double).
 hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed);
 size_t consensus_partials_needed(const gpga_ctx* c);
+// slot[0] = consensus distance of the live X (reduction pass + one final kernel).
+hipError_t launch_consensus_trace(gpga_ctx* c, double* slot);
 // slot[0] = sqrt(sum of `count` partials) (count = 0 stores 0): one entry of the consensus trace.
 hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot);
 // out[0] = mean of count floats (one workgroup, fp64 accumulation).

@@ -226,14 +226,16 @@ hipError_t launch_col_mean(const gpga_ctx* c, float* xbar) {
     return hipGetLastError();
 }
 
-hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
-    *partials_needed = consensus_partials_needed(c);
-    if (c->partials_cap < *partials_needed) return hipErrorOutOfMemory;
+// Per-workgroup partial sums of squared deviations of the live X into c->partials[1 ..];
+// *count receives their number.
+static hipError_t launch_consensus_partials(gpga_ctx* c, int64_t* count) {
+    *count = 0;
+    if (c->partials_cap < consensus_partials_needed(c)) return hipErrorOutOfMemory;
     const bool vec = aligned16(c->x) && (c->ld % 4 == 0);
     const int64_t nv = vec ? c->d / 4 : 0;
     const int64_t tail = c->d - nv * 4;
     const int64_t b1 = (nv + 255) / 256, b2 = (tail + 255) / 256;
-    double* parts = c->partials + 1;  // slot 0 holds the result
+    double* parts = c->partials + 1;  // slot 0 holds the result of the synchronous entry point
     if (b1 > 0) {
         hipLaunchKernelGGL((k_consensus<v4f>), dim3((unsigned)b1), dim3(256), 0, c->stream, c->x,
                            c->ld, (int64_t)0, nv, c->n, parts);
@@ -242,8 +244,24 @@ hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
         hipLaunchKernelGGL((k_consensus<float>), dim3((unsigned)b2), dim3(256), 0, c->stream, c->x,
                            c->ld, nv * 4, tail, c->n, parts + b1);
     }
-    hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(256), 0, c->stream, parts, b1 + b2, c->partials);
+    *count = b1 + b2;
     return hipGetLastError();
+}
+
+hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
+    *partials_needed = consensus_partials_needed(c);
+    int64_t count = 0;
+    const hipError_t e = launch_consensus_partials(c, &count);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(256), 0, c->stream, c->partials + 1, count, c->partials);
+    return hipGetLastError();
+}
+
+hipError_t launch_consensus_trace(gpga_ctx* c, double* slot) {
+    int64_t count = 0;
+    const hipError_t e = launch_consensus_partials(c, &count);
+    if (e != hipSuccess) return e;
+    return launch_trace_store(c, c->partials + 1, count, slot);
 }
 
 hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot) {

@@ -31,6 +31,9 @@ _TAG_X0 = 8
 _TAG_NODE_BIAS = 9
 _TAG_VLABEL = 10
 _TAG_GENERIC = 11
+_TAG_SIM_XSTAR = 12
+_TAG_SIM_FEAT = 13
+_TAG_SIM_LABEL = 14
 
 #: Named workloads.  ``H == 0`` encodes "never average" (H -> infinity).
 #: ``topologies`` lists the mixing graphs the workload is run with.
@@ -88,6 +91,26 @@ def logreg_problem(n: int, d: int, M: int, seed: int = 0, mu_var: float = 0.5,
         feat[i] = h.astype(np.float32)
         s = feat[i].astype(np.float64) @ xstar + label_noise_std * g_lab.standard_normal(M)
         y[i] = np.where(s >= 0.0, 1.0, -1.0)
+    return feat, y, xstar.astype(np.float32)
+
+
+def logreg_simulation_problem(n: int, d: int, M: int, seed: int = 0, iid: bool = False):
+    """Data of the paper's logistic-regression simulation (Sec. 5.1), as a recipe:
+
+    every feature vector h_{i,m} ~ N(0, 10 I_d) (covariance 10 I, i.e. std sqrt(10));
+    an auxiliary x*_i with N(0,1) entries, normalised to unit length, the same for
+    all nodes (iid) or one per node (non-iid); u ~ U(0,1) and the label is +1 if
+    u <= 1/(1 + exp(-h^T x*_i)), else -1.  The paper runs d = 10, M = 8000,
+    n = 20/50/100.  Returns feat (n,M,d) f32, y (n,M) f32, xstar (n,d) f32.
+    """
+    gx = _rng(seed, _TAG_SIM_XSTAR)
+    xs = gx.standard_normal((1 if iid else n, d))
+    xs /= np.linalg.norm(xs, axis=1, keepdims=True)
+    xstar = np.repeat(xs, n, axis=0) if iid else xs
+    feat = (math.sqrt(10.0) * _rng(seed, _TAG_SIM_FEAT).standard_normal((n, M, d))).astype(np.float32)
+    u = _rng(seed, _TAG_SIM_LABEL).random((n, M))
+    p = 1.0 / (1.0 + np.exp(-np.einsum("imd,id->im", feat.astype(np.float64), xstar)))
+    y = np.where(u <= p, 1.0, -1.0).astype(np.float32)
     return feat, y, xstar.astype(np.float32)
 
 
