@@ -64,6 +64,10 @@ def parse_args():
     ap.add_argument("--trace", type=int, default=-1,
                     help="1 = record the consensus distance after every step on the device (gpga_set_trace), "
                          "0 = do not; default: on for cfg5 (which reports it), off otherwise")
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark, measure the chip's plain read / write / copy rates with the "
+                         "library's streaming probe and the W = I fused step (3 reads : 2 writes, no mixing) on "
+                         "the cfg3 shape; prints one JSON line")
     ap.add_argument("--opt", action="append", default=[], help="launch option name=value (repeatable)")
     return ap.parse_args()
 
@@ -148,6 +152,61 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     return res
 
 
+def run_probe(reps=12):
+    """Machine ceilings: bytes moved / median launch time for the streaming probe kernels."""
+    import torch
+
+    from paper_2105_09080_amd import binding as B
+    from paper_2105_09080_amd import inputs
+    from paper_2105_09080_amd.harness import Simulation
+
+    nbytes = 6 << 30
+    stream = torch.cuda.Stream()
+    out = {}
+    with torch.cuda.stream(stream):
+        a, b, c2, m = (torch.zeros(nbytes // 4, dtype=torch.float32, device="cuda") for _ in range(4))
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+        cases = ((0, "read_only", nbytes), (1, "write_only", nbytes), (2, "copy_1r1w", 2 * nbytes),
+                 (3, "elementwise_3r2w", 5 * nbytes))
+        for bpc, tag in ((0, "one_lane_per_word"), (8, "grid_stride_8_per_cu")):
+            for kind, name, moved in cases:
+                dst = sink if kind == 0 else b
+                call = lambda: B.gpga_probe_stream(kind, a, dst, nbytes, stream.cuda_stream, src2=c2, inout=m,
+                                                   blocks_per_cu=bpc)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+                call()
+                ev[0].record()
+                for i in range(reps):
+                    call()
+                    ev[i + 1].record()
+                torch.cuda.synchronize()
+                ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+                out[f"{name}/{tag}"] = {"gbs_median": moved / ms[len(ms) // 2] / 1e6, "gbs_best": moved / ms[0] / 1e6,
+                                        "bytes": moved}
+    del a, b, c2, m
+    torch.cuda.empty_cache()
+    c = inputs.CONFIGS["cfg3"]
+    n, d = c["n"], c["d"]
+    sim = Simulation(n, d, topology="none", H=0, lr=c["lr"], momentum=c["momentum"], stream=stream)
+    sim.problem_synthetic(c["seed"], c["grad_var"])
+    with torch.cuda.stream(stream):
+        sim.local_grad()
+        for _ in range(3):
+            sim.step()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            sim.step()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
+    out["fused_step_W_identity_3r2w"] = {"gbs_median": BYTES_PER_ELT * n * d / ms[len(ms) // 2] / 1e6,
+                                         "gbs_best": BYTES_PER_ELT * n * d / ms[0] / 1e6,
+                                         "bytes": BYTES_PER_ELT * n * d}
+    sim.close()
+    return {"probe": "MI355X streaming rates, 128-bit non-temporal accesses", "peak_gbs": HBM_PEAK_GBS, **out}
+
+
 def cpu_baseline(cfg_name, topology, budget_s=15.0):
     """The oracle as it stands on a column slab of the workload (the recursion is
     column-separable with synthetic gradients), scaled to the full width."""
@@ -195,6 +254,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.probe:
+        print(json.dumps(run_probe()))
+        return
     opts = {}
     for o in args.opt:
         name, v = o.split("=")

@@ -250,6 +250,20 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * streaming a few rows at a time). */
 gpga_status gpga_set_option(gpga_ctx* ctx, const char* name, int64_t value);
 
+/* Measurement aid, not part of the method: a plain streaming kernel over `bytes`
+ * (a multiple of 16) per array of device memory on hip_stream, with the same 128-bit
+ * non-temporal accesses as the fused step.  kind 0 reads src_dev (dst_dev: any
+ * 4-byte device word, left unchanged); kind 1 writes dst_dev; kind 2 copies src_dev
+ * to dst_dev; kind 3 does the fused step's arithmetic on flat arrays: reads src_dev,
+ * src2_dev and inout_dev, writes inout_dev and dst_dev (3 reads : 2 writes, no row
+ * structure).  Unused pointers may be NULL.  blocks_per_cu = 0 launches one lane
+ * per 16-byte word; k > 0 launches k workgroups of 256 lanes per compute unit that
+ * stride over the words.  Timed by the caller; gives the rates of the chip against
+ * which the fused step's rate is to be read.  16-byte aligned pointers; EINVAL
+ * otherwise.  Needs no context. */
+gpga_status gpga_probe_stream(int32_t kind, const float* src_dev, float* dst_dev, const float* src2_dev,
+                              float* inout_dev, int64_t bytes, int32_t blocks_per_cu, void* hip_stream);
+
 const char* gpga_last_error(const gpga_ctx* ctx);
 const char* gpga_version(void);
 

@@ -63,6 +63,8 @@ SIGNATURES = [
     ("gpga_mean", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_current_x", _c.c_int, [_ctx_p, _c.POINTER(_c.c_void_p)]),
     ("gpga_set_option", _c.c_int, [_ctx_p, _c.c_char_p, _c.c_int64]),
+    ("gpga_probe_stream", _c.c_int, [_c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64,
+                                     _c.c_int32, _c.c_void_p]),
     ("gpga_last_error", _c.c_char_p, [_ctx_p]),
     ("gpga_version", _c.c_char_p, []),
 ]
@@ -273,6 +275,15 @@ def gpga_current_x(ctx) -> int:
 
 def gpga_set_option(ctx, name: str, value: int):
     _check(ctx, _lib.gpga_set_option(ctx, name.encode(), value))
+
+
+def gpga_probe_stream(kind: int, src, dst, nbytes: int, stream=None, src2=None, inout=None, blocks_per_cu: int = 0):
+    """kind 0 read src (dst: 4-byte sink), 1 write dst, 2 copy src -> dst, 3 read src, src2, inout and
+    write inout, dst; enqueued on ``stream``."""
+    status = _lib.gpga_probe_stream(kind, _ptr(src), _ptr(dst), _ptr(src2), _ptr(inout), nbytes, blocks_per_cu,
+                                    stream)
+    if status != GPGA_OK:
+        raise GpgaError(status, "gpga_probe_stream rejected its arguments or failed to launch")
 
 
 def gpga_last_error(ctx) -> str:

@@ -753,6 +753,29 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     return GPGA_OK;
 }
 
+gpga_status gpga_probe_stream(int32_t kind, const float* src_dev, float* dst_dev, const float* src2_dev,
+                              float* inout_dev, int64_t bytes, int32_t blocks_per_cu, void* hip_stream) {
+    if (kind < 0 || kind > 3 || bytes < 16 || bytes % 16 || blocks_per_cu < 0) return GPGA_EINVAL;
+    const bool need_src = kind != 1, need_dst = kind != 0, need_more = kind == 3;
+    if (need_src && (!src_dev || !aligned(src_dev, 16))) return GPGA_EINVAL;
+    if (need_dst && (!dst_dev || !aligned(dst_dev, 16))) return GPGA_EINVAL;
+    if (kind == 0 && (!dst_dev || !aligned(dst_dev, 4))) return GPGA_EINVAL;  // 4-byte sink of the read probe
+    if (need_more && (!src2_dev || !inout_dev || !aligned(src2_dev, 16) || !aligned(inout_dev, 16)))
+        return GPGA_EINVAL;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess) return GPGA_EDEVICE;
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const int64_t count = bytes / 16;
+    int64_t blocks = (count + 255) / 256;  // one 16-byte word per lane ...
+    if (blocks_per_cu > 0 && blocks > (int64_t)cus * blocks_per_cu)
+        blocks = (int64_t)cus * blocks_per_cu;  // ... or a capped grid that strides over the words
+    if (blocks > 0x7fffffffLL) return GPGA_EINVAL;
+    const hipError_t e = launch_probe_stream(kind, src_dev, dst_dev, src2_dev, inout_dev, count,
+                                             kind == 0 ? dst_dev : nullptr, blocks,
+                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? GPGA_OK : GPGA_EDEVICE;
+}
+
 const char* gpga_last_error(const gpga_ctx* c) { return c ? c->err : "null context"; }
 
 }  // extern "C"

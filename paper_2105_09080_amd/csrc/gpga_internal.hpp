@@ -170,5 +170,8 @@ size_t consensus_partials_needed(const gpga_ctx* c);
 hipError_t launch_consensus_trace(gpga_ctx* c, double* slot);
 // slot[0] = sqrt(sum of `count` partials) (count = 0 stores 0): one entry of the consensus trace.
 hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot);
+// Streaming probe over count16 16-byte words (kind 0 read, 1 write, 2 copy, 3 three reads : two writes).
+hipError_t launch_probe_stream(int kind, const float* src, float* dst, const float* src2, float* inout,
+                               int64_t count16, float* sink, int64_t blocks, hipStream_t st);
 // out[0] = mean of count floats (one workgroup, fp64 accumulation).
 hipError_t launch_mean_f32(const gpga_ctx* c, const float* v, int64_t count, double* out);

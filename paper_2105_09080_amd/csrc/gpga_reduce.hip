@@ -189,7 +189,53 @@ __global__ void __launch_bounds__(256) k_fill_rows(float* __restrict__ dst, int6
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Plain streaming kernels used to measure what this chip's memory system delivers
+// for reads, writes and copies (the context in which the fused step's rate is read).
+// kind 0: read only (the sum keeps the loads alive), kind 1: write only, kind 2: copy
+// src -> dst, kind 3: the fused step's arithmetic on flat arrays (read src, src2,
+// inout; write inout, dst).  128-bit non-temporal accesses, consecutive lanes on
+// consecutive 16-byte words; one word per lane, or grid-stride when the grid is capped.
+template <int KIND>
+__global__ void __launch_bounds__(256) k_probe_stream(const v4f* __restrict__ src, v4f* __restrict__ dst,
+                                                      const v4f* __restrict__ src2, v4f* __restrict__ inout,
+                                                      int64_t count, float* __restrict__ sink) {
+    v4f acc = v4f(0);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+#pragma unroll 4
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < count; t += stride) {
+        if (KIND == 0) acc += ld_stream(src + t);
+        if (KIND == 1) __builtin_nontemporal_store(v4f(1.0f), dst + t);
+        if (KIND == 2) __builtin_nontemporal_store(ld_stream(src + t), dst + t);
+        if (KIND == 3) {  // the fused step's mix without any row structure: 3 reads, 2 writes
+            const v4f xv = ld_stream(src + t), mv = ld_stream(inout + t), gv = ld_stream(src2 + t);
+            const v4f mom = 0.9f * mv + gv;
+            __builtin_nontemporal_store(mom, inout + t);
+            __builtin_nontemporal_store(xv - 0.1f * mom, dst + t);
+        }
+    }
+    if (KIND == 0) {
+        float v = acc.x + acc.y + acc.z + acc.w;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+        if ((threadIdx.x & (kWave - 1)) == 0 && v == 12345.678f) atomicAdd(sink, v);  // practically never taken
+    }
+}
+
 }  // namespace
+
+hipError_t launch_probe_stream(int kind, const float* src, float* dst, const float* src2, float* inout,
+                               int64_t count16, float* sink, int64_t blocks, hipStream_t st) {
+    const v4f* s = reinterpret_cast<const v4f*>(src);
+    v4f* d = reinterpret_cast<v4f*>(dst);
+    const v4f* s2 = reinterpret_cast<const v4f*>(src2);
+    v4f* io = reinterpret_cast<v4f*>(inout);
+    const dim3 grid((unsigned)blocks), block(256);
+    if (kind == 0) hipLaunchKernelGGL((k_probe_stream<0>), grid, block, 0, st, s, d, s2, io, count16, sink);
+    else if (kind == 1) hipLaunchKernelGGL((k_probe_stream<1>), grid, block, 0, st, s, d, s2, io, count16, sink);
+    else if (kind == 2) hipLaunchKernelGGL((k_probe_stream<2>), grid, block, 0, st, s, d, s2, io, count16, sink);
+    else hipLaunchKernelGGL((k_probe_stream<3>), grid, block, 0, st, s, d, s2, io, count16, sink);
+    return hipGetLastError();
+}
 
 size_t consensus_partials_needed(const gpga_ctx* c) {
     // vector pass workgroups + scalar tail workgroup + 1 result slot
