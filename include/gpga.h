@@ -173,6 +173,15 @@ gpga_status gpga_local_loss(gpga_ctx* ctx, const int32_t* batch_idx_dev, int32_t
  * m and x_new once; then swaps x / x_new and increments k. */
 gpga_status gpga_step(gpga_ctx* ctx);
 
+/* The loop of Algorithm 1: T iterations, each gpga_local_grad followed by
+ * gpga_step, enqueued from one call (no per-iteration trip through the caller;
+ * nothing synchronises).  batch_table_dev: T x n x B int32 on the device, iteration
+ * j of this call uses rows [j*n*B, (j+1)*n*B); NULL with B = 0 means full batches
+ * (and is what the synthetic problem takes).  Stops at the first failing call and
+ * returns its status; iterations before it stay enqueued.  Not for contexts with
+ * adaptive averaging (ESTATE). */
+gpga_status gpga_run(gpga_ctx* ctx, int64_t T, const int32_t* batch_table_dev, int32_t B);
+
 /* Attach an arbitrary weight matrix W (Sec. 3: W >= 0, W 1 = 1, 1^T W = 1^T,
  * w_ij > 0 only for neighbours and i = j) in compressed-row form and switch the
  * context to GPGA_TOPO_CUSTOM.  All three arrays are in HOST memory and are

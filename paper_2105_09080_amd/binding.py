@@ -49,6 +49,7 @@ SIGNATURES = [
     ("gpga_local_grad", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int32]),
     ("gpga_local_loss", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int32, _c.c_void_p]),
     ("gpga_step", _c.c_int, [_ctx_p]),
+    ("gpga_run", _c.c_int, [_ctx_p, _c.c_int64, _c.c_void_p, _c.c_int32]),
     ("gpga_set_mixing_csr", _c.c_int, [_ctx_p, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int32),
                                        _c.POINTER(_c.c_float)]),
     ("gpga_mixing_beta", _c.c_int, [_ctx_p, _c.POINTER(_c.c_double)]),
@@ -238,6 +239,10 @@ def gpga_check_mixing_csr(n: int, row_ptr, col, val) -> float:
     if status != GPGA_OK:
         raise GpgaError(status, "mixing matrix rejected")
     return out.value
+
+
+def gpga_run(ctx, T: int, batch_table=None, B: int = 0):
+    _check(ctx, _lib.gpga_run(ctx, T, _ptr(batch_table), B))
 
 
 def gpga_aga_enable(ctx, H_init: int, warmup_iters: int, H_max: int):

@@ -624,6 +624,24 @@ gpga_status gpga_check_mixing_csr(int32_t n, const int64_t* row_ptr_host, const 
     return GPGA_OK;
 }
 
+gpga_status gpga_run(gpga_ctx* c, int64_t T, const int32_t* batch_table_dev, int32_t B) {
+    if (!c) return GPGA_EINVAL;
+    if (T < 0) return fail(c, GPGA_EINVAL, "T must be >= 0");
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    if (c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is enabled: iterate with gpga_aga_step");
+    if (c->problem == PROB_NONE) return fail(c, GPGA_ESTATE, "no problem attached (gpga_problem_*)");
+    DeviceGuard guard(c->device);
+    const int64_t stride = batch_table_dev ? (int64_t)c->n * B : 0;
+    for (int64_t j = 0; j < T; ++j) {
+        gpga_status s = run_grad(c, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, nullptr);
+        if (s != GPGA_OK) return s;
+        const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
+        s = run_step(c, global);
+        if (s != GPGA_OK) return s;
+    }
+    return GPGA_OK;
+}
+
 gpga_status gpga_aga_enable(gpga_ctx* c, int64_t H_init, int64_t warmup_iters, int64_t H_max) {
     if (!c) return GPGA_EINVAL;
     if (H_init < 1 || H_max < H_init || warmup_iters < 0)

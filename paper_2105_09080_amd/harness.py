@@ -135,6 +135,14 @@ class Simulation:
         """Step size the next step will use."""
         return B.gpga_lr(self.ctx)
 
+    def run(self, T: int, batch_table=None):
+        """T iterations (gradient + step) from one call; batch_table: (>= T, n, B) int32 device tensor."""
+        if batch_table is None:
+            B.gpga_run(self.ctx, T, None, 0)
+        else:
+            assert batch_table.shape[0] >= T and batch_table.is_contiguous()
+            B.gpga_run(self.ctx, T, batch_table, batch_table.shape[-1])
+
     def aga_enable(self, H_init: int, warmup_iters: int, H_max: int):
         B.gpga_aga_enable(self.ctx, H_init, warmup_iters, H_max)
 

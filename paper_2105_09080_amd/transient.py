@@ -70,12 +70,14 @@ def run_method(method: str, topology: str, n: int, d: int, feat, y, idx, *, H: i
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     with torch.cuda.stream(stream):
-        for k in range(T):
-            sim.local_grad(idx_dev[k])
-            sim.step()
-            if (k + 1) % eval_every == 0:
+        k = 0
+        while k < T:
+            chunk = min(eval_every, T - k)
+            sim.run(chunk, idx_dev[k:k + chunk])          # the loop of Algorithm 1, enqueued by one call
+            k += chunk
+            if k % eval_every == 0:
                 losses.append(probe(sim))
-                at.append(k + 1)
+                at.append(k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     out = {"method": method, "topology": topo_override or topology, "n": n, "H": period(H), "iters": T,

@@ -56,3 +56,42 @@ def test_resumed_run_continues_bit_for_bit(hx, n, d, topology, nesterov):
     # and a second uninterrupted run reproduces the first exactly
     Xc, Mc, _, trc = _run(hx, n, d, topology, H, T, nesterov=nesterov, trace_len=T)
     assert np.array_equal(Xa, Xc) and np.array_equal(Ma, Mc) and np.array_equal(tra, trc)
+
+
+@pytest.mark.parametrize("problem", ["lsq", "logreg", "synthetic"])
+def test_run_equals_stepping_one_iteration_at_a_time(hx, problem):
+    from paper_2105_09080_amd import binding as B
+    n, d, M, Bsz, T, H = 8, 1003, 40, 6, 23, 4
+    sims = []
+    for _ in range(2):
+        sim = hx.Simulation(n, d, topology="expo1", H=H, lr=0.02, momentum=0.9)
+        idx_d = None
+        if problem == "lsq":
+            A, b, _ = inputs.lsq_problem(n, d, M, seed=2)
+            sim.problem_lsq(A, b)
+        elif problem == "logreg":
+            feat, y, _ = inputs.logreg_problem(n, d, M, seed=2)
+            sim.problem_logreg((feat / np.sqrt(d)).astype(np.float32), y)
+            idx_d = sim.upload_batches(inputs.batch_indices(T, n, Bsz, M, seed=2))
+        else:
+            sim.problem_synthetic(5, 1e-2)
+        sims.append((sim, idx_d))
+    (a, idx_a), (b_, idx_b) = sims
+    for k in range(T):
+        a.local_grad(None if idx_a is None else idx_a[k])
+        a.step()
+    b_.run(10, idx_b)                                    # two calls: the table advances with the caller's slice
+    b_.run(T - 10, None if idx_b is None else idx_b[10:])
+    torch.cuda.synchronize()
+    assert a.k == b_.k == T
+    assert torch.equal(a.X, b_.X) and torch.equal(a.M, b_.M)
+    b_.run(0, idx_b)                                     # zero iterations: nothing happens
+    assert b_.k == T
+    with pytest.raises(B.GpgaError) as e:
+        B.gpga_run(b_.ctx, -1, None, 0)
+    assert e.value.status == B.GPGA_EINVAL
+    b_.aga_enable(2, 0, 8)
+    with pytest.raises(B.GpgaError) as e:
+        b_.run(1, idx_b)
+    assert e.value.status == B.GPGA_ESTATE
+    a.close(), b_.close()
