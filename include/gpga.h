@@ -158,7 +158,8 @@ gpga_status gpga_problem_synthetic(gpga_ctx* ctx, uint64_t seed, float grad_var)
 /* g_i = grad F_i(x_i^(k); xi_i) for every node i at its own current row x_i,
  * written to g_dev.  batch_idx_dev: n x B int32 sample indices in [0, M) (the
  * minibatch xi_i, drawn by the caller); NULL with B = 0 means the full local
- * dataset.  Ignored for the synthetic problem.  ESTATE without bind/problem. */
+ * dataset.  The kernels check every index: one outside [0, M) is never used as an
+ * address, and the gradient row (and loss) of its node comes out as NaN.  Ignored for the synthetic problem.  ESTATE without bind/problem. */
 gpga_status gpga_local_grad(gpga_ctx* ctx, const int32_t* batch_idx_dev, int32_t B);
 
 /* Loss companion of gpga_local_grad (used by adaptive averaging, Alg. 2):

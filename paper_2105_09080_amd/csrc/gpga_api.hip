@@ -209,6 +209,7 @@ gpga_status run_grad(gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out
     int32_t Beff = 0;
     gpga_status s = check_batch(c, idx, B, &Beff);
     if (s != GPGA_OK) return s;
+    if (c->n > 65535) return fail(c, GPGA_EINVAL, "the gradient kernels take n <= 65535 nodes (one grid row per node)");
     DeviceGuard guard(c->device);
     hipError_t e = hipSuccess;
     if (c->problem == PROB_SYNTH) {

@@ -151,6 +151,13 @@ __global__ void __launch_bounds__(256) k_rows_margin(const float* __restrict__ f
     __shared__ double s_buf[4];
     const int b = blockIdx.x, i = blockIdx.y;
     const int32_t r = idx ? idx[(int64_t)i * B + b] : b;
+    if (r < 0 || r >= M) {  // a sample index outside [0, M): no access, the node's gradient and loss become NaN
+        if (threadIdx.x == 0) {
+            coef[(int64_t)i * B + b] = __builtin_nanf("");
+            lossterm[(int64_t)i * B + b] = __builtin_nanf("");
+        }
+        return;
+    }
     const float* __restrict__ f = feat + ((int64_t)i * M + r) * d;
     const float* __restrict__ xi = x + (int64_t)i * ld;
     double acc = 0.0;
@@ -191,7 +198,8 @@ __global__ void __launch_bounds__(256) k_rows_accum(const float* __restrict__ fe
         if (t * 4 >= d) return;
         double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
         for (int b = 0; b < B; ++b) {
-            const int32_t r = ii ? ii[b] : b;
+            int32_t r = ii ? ii[b] : b;
+            if (r < 0 || r >= M) r = 0;  // its coefficient is NaN (set by the margin pass): row 0 is only a safe address
             const v4f fv = reinterpret_cast<const v4f*>(fi + (int64_t)r * d)[t];
             const double cb = ci[b];
             a0 += cb * fv.x;
@@ -209,7 +217,8 @@ __global__ void __launch_bounds__(256) k_rows_accum(const float* __restrict__ fe
         if (t >= d) return;
         double a0 = 0;
         for (int b = 0; b < B; ++b) {
-            const int32_t r = ii ? ii[b] : b;
+            int32_t r = ii ? ii[b] : b;
+            if (r < 0 || r >= M) r = 0;
             a0 += (double)ci[b] * fi[(int64_t)r * d + t];
         }
         gi[t] = (float)a0;
@@ -289,7 +298,13 @@ __global__ void k_virtual_coef(const double* __restrict__ zpart, const float* __
     if (t >= (int64_t)n * B) return;
     const int i = (int)(t / B);
     float cf, ls;
-    sample_terms<PROB_LOGREG>(zpart[t], y[(int64_t)i * M + idx[t]], 1.0f / (float)B, &cf, &ls);
+    const int32_t r = idx[t];
+    if (r < 0 || r >= M) {  // label index outside [0, M): no access, NaN marks the node's gradient and loss
+        coef[t] = __builtin_nanf("");
+        lossterm[t] = __builtin_nanf("");
+        return;
+    }
+    sample_terms<PROB_LOGREG>(zpart[t], y[(int64_t)i * M + r], 1.0f / (float)B, &cf, &ls);
     coef[t] = cf;
     lossterm[t] = ls;
 }

@@ -566,3 +566,37 @@ def test_gossip_aga_trajectory_and_period_sequence(hx, topology):
     with pytest.raises(Exception):
         sim.step()                                            # plain step is refused while AGA is on
     sim.close()
+
+
+def test_out_of_range_sample_indices_poison_only_their_node_and_touch_nothing(hx):
+    # indices outside [0, M) are checked by the kernels: never used as an address, the node's
+    # gradient row and loss become NaN, every other node is computed as usual
+    n, d, M, B = 4, 1003, 20, 6
+    feat, y, _ = inputs.logreg_problem(n, d, M, seed=9)
+    idx = inputs.batch_indices(1, n, B, M, seed=9)[0].copy()
+    bad = idx.copy()
+    bad[1, 2] = M              # one past the end
+    bad[3, 0] = -1
+    sim = hx.Simulation(n, d, topology="ring", H=0, lr=0.1, momentum=0.0)
+    sim.problem_logreg(feat, y)
+    idx_d = sim.upload_batches(np.stack([idx, bad]))
+    X = inputs.random_state(n, d, seed=9)[0]
+    sim.set_state(X=X)
+    sim.local_grad(idx_d[1])
+    G_bad = host(sim.G)
+    loss_bad = host(sim.local_loss(idx_d[1]))
+    G_ref = orc.logreg_grad(feat, y, X.astype(np.float64), idx)
+    assert np.isnan(G_bad[1]).all() and np.isnan(G_bad[3]).all()
+    assert np.isnan(loss_bad[[1, 3]]).all() and np.isfinite(loss_bad[[0, 2]]).all()
+    assert_close(G_bad[[0, 2]], G_ref[[0, 2]], TOL_STEP, "untouched nodes")
+    sim.close()
+    # the virtual-feature problem reads labels through the same indices
+    yv = inputs.virtual_labels(n, M, seed=9)
+    sim = hx.Simulation(n, d, topology="ring", H=0, lr=0.1, momentum=0.0)
+    sim.problem_logreg_virtual(9, yv, 0.5)
+    idx_d = sim.upload_batches(np.stack([idx, bad]))
+    sim.set_state(X=X)
+    sim.local_grad(idx_d[1])
+    G_bad = host(sim.G)
+    assert np.isnan(G_bad[1]).all() and np.isnan(G_bad[3]).all() and np.isfinite(G_bad[[0, 2]]).all()
+    sim.close()
