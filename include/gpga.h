@@ -82,6 +82,7 @@ gpga_status gpga_destroy(gpga_ctx* ctx);
  *   g_dev     stochastic gradients G^(k): written by gpga_local_grad, or by the
  *             caller itself (e.g. a real backward pass) before gpga_step
  * After each gpga_step the roles of x_dev and x_new_dev swap (gpga_current_x).
+ * No two of the four arrays may overlap (EINVAL).
  * Pointers must be 4-byte aligned; 16-byte aligned pointers with ld % 4 == 0
  * take the 128-bit path.  hip_stream is a hipStream_t (NULL = default stream). */
 gpga_status gpga_bind(gpga_ctx* ctx, float* x_dev, float* x_new_dev, float* m_dev,

@@ -315,10 +315,21 @@ gpga_status gpga_bind(gpga_ctx* c, float* x, float* x_new, float* m, float* g, i
     if (!c) return GPGA_EINVAL;
     if (!x || !x_new || !g) return fail(c, GPGA_EINVAL, "x, x_new and g must not be NULL");
     if (!m && c->mu != 0.f) return fail(c, GPGA_EINVAL, "m may be NULL only when momentum == 0");
-    if (x == x_new) return fail(c, GPGA_EINVAL, "x_new must not alias x");
     if (ld < c->d) return fail(c, GPGA_EINVAL, "ld = %lld is smaller than d = %lld", (long long)ld, (long long)c->d);
     if (!aligned(x, 4) || !aligned(x_new, 4) || !aligned(g, 4) || (m && !aligned(m, 4)))
         return fail(c, GPGA_EINVAL, "buffers must be 4-byte aligned");
+    {   // the four n x ld arrays must not overlap: every kernel reads some while writing others
+        const float* bufs[4] = {x, x_new, g, m};
+        const char* names[4] = {"x", "x_new", "g", "m"};
+        const uintptr_t span = (uintptr_t)c->n * (uintptr_t)ld * sizeof(float);
+        for (int p = 0; p < 4; ++p)
+            for (int q = p + 1; q < 4; ++q) {
+                if (!bufs[p] || !bufs[q]) continue;
+                const uintptr_t lo = reinterpret_cast<uintptr_t>(bufs[p]), hi = reinterpret_cast<uintptr_t>(bufs[q]);
+                if ((lo <= hi ? hi - lo : lo - hi) < span)
+                    return fail(c, GPGA_EINVAL, "%s and %s overlap", names[p], names[q]);
+            }
+    }
     c->x = x;
     c->x_new = x_new;
     c->m = m;

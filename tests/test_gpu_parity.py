@@ -518,10 +518,16 @@ def test_error_paths_return_status_codes(hx):
     with pytest.raises(B.GpgaError) as e:
         B.gpga_bind(ctx, t, t, t2, t2, 8)          # x_new aliases x
     assert e.value.status == B.GPGA_EINVAL
+    m0, g0 = torch.zeros((4, 8), device="cuda"), torch.zeros((4, 8), device="cuda")
+    big = torch.zeros(4 * 8 + 16, device="cuda")
+    for args in ((t, t2, g0, g0), (t, t2, t, g0), (t, t2, m0, t2), (big[:32], big[16:48], m0, g0)):
+        with pytest.raises(B.GpgaError) as e:       # any two of the four arrays overlapping
+            B.gpga_bind(ctx, *args, 8)
+        assert e.value.status == B.GPGA_EINVAL and "overlap" in str(e.value)
     with pytest.raises(B.GpgaError):
         B.gpga_bind(ctx, t, t2, None, t2, 8)       # momentum != 0 needs m
     with pytest.raises(B.GpgaError):
-        B.gpga_bind(ctx, t, t2, t2, t2, 4)         # ld < d
+        B.gpga_bind(ctx, t, t2, m0, g0, 4)         # ld < d
     m, g = torch.zeros((4, 8), device="cuda"), torch.zeros((4, 8), device="cuda")
     B.gpga_bind(ctx, t, t2, m, g, 8)
     with pytest.raises(B.GpgaError) as e:
