@@ -27,6 +27,8 @@
 // of the workgroup); partial column sums are combined with a wavefront
 // shuffle (xor butterfly) and then an LDS tree across waves.  Every row gets
 // the same bits of the mean, so the rows are bit-identical afterwards.
+#include <type_traits>
+
 #include "gpga_internal.hpp"
 
 namespace {
@@ -436,6 +438,20 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
     uint32_t units_done = 0;
 
+    // deferred mean of the previous whole tile of this wavefront (see below)
+    T prev_mean = T(0);
+    T* prev_xnp = nullptr;
+    bool have_prev = false;  // wave-uniform
+    auto flush_prev = [&]() {
+        for (int row = 0; row < n; row += U) {
+            pace_wait(a.pace, t0, units_done);
+            units_done += U;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (row + u < n) st_stream(prev_xnp + (int64_t)(row + u) * ldT, prev_mean);
+        }
+    };
+
     for (int64_t bx = blockIdx.x; bx < a.gx; bx += gridDim.x) {
         const int64_t tile = logical_block(bx, a.gx, a.xcd) * a.tpb + tile_l;
         const int64_t col = tile * CL + lane_c;
@@ -448,80 +464,101 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + coff;
 
         T sum = T(0);
-        if (on && RS == 1) {
-            // One lane walks all n rows of its column group: same software pipeline
-            // as the gossip walk (next batch's loads are issued ahead of this
-            // batch's stores of m; branch-free hot loop).
+        // One lane walks all n rows of its column group (large problems).  The n copies of
+        // a tile's mean are not written in a burst of their own: they are DEFERRED and
+        // stored row by row while the next tile of this wavefront is being read, so that
+        // the chip sees the same steady 3-read : 2-write mix as in the gossip walk.  Only
+        // whole tiles take this path (the ragged last tile falls through to the plain one).
+        const bool whole_tile = (tile + 1) * CL <= a.ge.ncols;  // wave-uniform
+        if (RS == 1 && whole_tile) {
+            // Same software pipeline as the gossip walk: next batch's loads are issued
+            // ahead of this batch's stores; branch-free hot loop.
             struct Batch {
                 T xv[U], mv[U], gv[U];
             };
-            int row = 0;
-            auto load_full = [&](Batch& b) {
-                pace_wait(a.pace, t0, units_done);
-                units_done += U * kReadUnits;
+            auto rows_pass = [&](auto with_prev) {
+                constexpr bool WP = decltype(with_prev)::value;
+                constexpr uint32_t kUnits = kReadUnits + (WP ? 1u : 0u);
+                int row = 0;
+                auto load_full = [&](Batch& b) {
+                    pace_wait(a.pace, t0, units_done);
+                    units_done += U * kUnits;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t off = (int64_t)(row + u) * ldT;
-                    b.xv[u] = ld_stream(xp + off);
-                    if (MOM) b.mv[u] = ld_stream(mp + off);
-                    b.gv[u] = ld_stream(gp + off);
-                }
-                row += U;
-            };
-            auto process_full = [&](const Batch& b, int first_row) {
-                T part = T(0);
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    T mom = b.gv[u];
-                    if (MOM) {
-                        mom = mu * b.mv[u] + b.gv[u];
-                        st_stream(mp + (int64_t)(first_row + u) * ldT, mom);
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t off = (int64_t)(row + u) * ldT;
+                        b.xv[u] = ld_stream(xp + off);
+                        if (MOM) b.mv[u] = ld_stream(mp + off);
+                        b.gv[u] = ld_stream(gp + off);
                     }
-                    part += half_step<MOM>(b.xv[u], b.gv[u], mom, lr, mu);
-                }
-                sum += part;
-            };
-            const int nfull = n / U;
-            Batch A, B;
-            int done = 0;
-            if (nfull >= 1) {
-                load_full(A);
-                int b = 0;
-                for (; b + 3 <= nfull; b += 2) {
-                    load_full(B);
-                    __builtin_amdgcn_sched_barrier(0);
-                    process_full(A, done);
-                    __builtin_amdgcn_sched_barrier(0);
+                    row += U;
+                };
+                auto process_full = [&](const Batch& b, int first_row) {
+                    T part = T(0);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        T mom = b.gv[u];
+                        if (MOM) {
+                            mom = mu * b.mv[u] + b.gv[u];
+                            st_stream(mp + (int64_t)(first_row + u) * ldT, mom);
+                        }
+                        if (WP) st_stream(prev_xnp + (int64_t)(first_row + u) * ldT, prev_mean);
+                        part += half_step<MOM>(b.xv[u], b.gv[u], mom, lr, mu);
+                    }
+                    sum += part;
+                };
+                const int nfull = n / U;
+                Batch A, B;
+                int done = 0;
+                if (nfull >= 1) {
                     load_full(A);
-                    __builtin_amdgcn_sched_barrier(0);
-                    process_full(B, done + U);
-                    __builtin_amdgcn_sched_barrier(0);
-                    done += 2 * U;
+                    int b = 0;
+                    for (; b + 3 <= nfull; b += 2) {
+                        load_full(B);
+                        __builtin_amdgcn_sched_barrier(0);
+                        process_full(A, done);
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_full(A);
+                        __builtin_amdgcn_sched_barrier(0);
+                        process_full(B, done + U);
+                        __builtin_amdgcn_sched_barrier(0);
+                        done += 2 * U;
+                    }
+                    if (nfull - b == 2) {
+                        load_full(B);
+                        __builtin_amdgcn_sched_barrier(0);
+                        process_full(A, done);
+                        process_full(B, done + U);
+                        done += 2 * U;
+                    } else {
+                        process_full(A, done);
+                        done += U;
+                    }
                 }
-                if (nfull - b == 2) {
-                    load_full(B);
-                    __builtin_amdgcn_sched_barrier(0);
-                    process_full(A, done);
-                    process_full(B, done + U);
-                    done += 2 * U;
-                } else {
-                    process_full(A, done);
-                    done += U;
+                for (; done < n; ++done) {
+                    const int64_t off = (int64_t)done * ldT;
+                    const T xv = ld_stream(xp + off);
+                    const T gv = ld_stream(gp + off);
+                    T mom = gv;
+                    if (MOM) {
+                        mom = mu * ld_stream(mp + off) + gv;
+                        st_stream(mp + off, mom);
+                    }
+                    if (WP) st_stream(prev_xnp + off, prev_mean);
+                    units_done += kUnits;
+                    sum += half_step<MOM>(xv, gv, mom, lr, mu);
                 }
-            }
-            for (; done < n; ++done) {
-                const int64_t off = (int64_t)done * ldT;
-                const T xv = ld_stream(xp + off);
-                const T gv = ld_stream(gp + off);
-                T mom = gv;
-                if (MOM) {
-                    mom = mu * ld_stream(mp + off) + gv;
-                    st_stream(mp + off, mom);
-                }
-                units_done += kReadUnits;
-                sum += half_step<MOM>(xv, gv, mom, lr, mu);
-            }
-        } else if (on) {
+            };
+            if (have_prev) rows_pass(std::true_type{}); else rows_pass(std::false_type{});
+            prev_mean = sum * a.inv_n;
+            prev_xnp = xnp;
+            have_prev = true;
+            continue;
+        }
+        if (have_prev) {  // a tile that writes at once follows: nothing may stay deferred behind it
+            flush_prev();
+            have_prev = false;
+        }
+        if (on) {
             for (int base = r0; base < n; base += RS * U) {
                 T xv[U], mv[U], gv[U];
                 pace_wait(a.pace, t0, units_done);
@@ -580,6 +617,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
             }
         }
     }
+    if (have_prev) flush_prev();
 }
 
 int gcd_i(int a, int b) {
@@ -702,7 +740,7 @@ constexpr int64_t kPacedWaves = 2048;
 constexpr int kAutoBlocksPerCu = 4;
 constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
 constexpr double kAutoPaceGbsShort = 6000.0;   // walks over cycles of 8 rows
-constexpr double kAutoPaceGbsGlobal = 5950.0;  // the global-average kernel saturates a little lower
+constexpr double kAutoPaceGbsGlobal = 6300.0;  // same stream mix as the walk once the mean rows are deferred
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
 LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool walks_rows, double auto_gbs) {
