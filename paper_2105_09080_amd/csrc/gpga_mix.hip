@@ -20,6 +20,7 @@
 //    all rows of a column tile run together and re-reads of y hit the caches
 //    (28 B per element of HBM traffic when they do).
 #include "gpga_internal.hpp"
+#include "gpga_pace.hpp"
 
 namespace {
 
@@ -48,6 +49,8 @@ struct CsrDev {
 struct TileArgs {
     StepGeom ge;
     CsrDev w;
+    int64_t tiles;  // column tiles; workgroups stride over them
+    PaceArgs pace;
 };
 
 constexpr int kTileWavesDefault = 4;
@@ -67,84 +70,98 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
     const int n = a.ge.n;
     const int64_t ldT = a.ge.ld / V;
     const float lr = a.ge.lr, mu = a.ge.mu;
-    const int64_t col = (int64_t)blockIdx.x * kWave + lane;
-    const bool on = col < a.ge.ncols;
+    constexpr uint32_t kLoadUnits = MOM ? 4u : 2u;  // 4-byte streams per row in phase 1 (reads + the m store)
+    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    uint32_t units_done = 0;
 
-    const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
-    const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
-    T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
-    T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+    // Workgroups stride over the column tiles (one tile each in the default one-shot launch).
+    // A paced launch has exactly the resident workgroups: they then read the same row group
+    // of their tiles at the same time and later store the same output rows.
+    for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+        const int64_t col = tile * kWave + lane;
+        const bool on = col < a.ge.ncols;
 
-    // Phase 1: rows wave, wave + 4, ... : local update, y into LDS.
-    for (int base = wave; base < n; base += kTileWaves * kTileUnroll) {
-        T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+
+        // Phase 1: rows wave, wave + W, ... : local update, y into LDS.
+        for (int base = wave; base < n; base += kTileWaves * kTileUnroll) {
+            T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
+            pace_wait(a.pace, t0, units_done);
+            units_done += kTileUnroll * kLoadUnits;
 #pragma unroll
-        for (int u = 0; u < kTileUnroll; ++u) {
-            const int row = base + u * kTileWaves;
-            if (row < n && on) {
-                const int64_t off = (int64_t)row * ldT;
-                xv[u] = ld_stream(xp + off);
-                if (MOM) mv[u] = ld_stream(mp + off);
-                gv[u] = ld_stream(gp + off);
+            for (int u = 0; u < kTileUnroll; ++u) {
+                const int row = base + u * kTileWaves;
+                if (row < n && on) {
+                    const int64_t off = (int64_t)row * ldT;
+                    xv[u] = ld_stream(xp + off);
+                    if (MOM) mv[u] = ld_stream(mp + off);
+                    gv[u] = ld_stream(gp + off);
+                }
             }
-        }
 #pragma unroll
-        for (int u = 0; u < kTileUnroll; ++u) {
-            const int row = base + u * kTileWaves;
-            if (row < n) {
-                T y = T(0);
-                if (on) {
-                    T mom = gv[u];
-                    if (MOM) {
-                        mom = mu * mv[u] + gv[u];
-                        st_stream(mp + (int64_t)row * ldT, mom);
+            for (int u = 0; u < kTileUnroll; ++u) {
+                const int row = base + u * kTileWaves;
+                if (row < n) {
+                    T y = T(0);
+                    if (on) {
+                        T mom = gv[u];
+                        if (MOM) {
+                            mom = mu * mv[u] + gv[u];
+                            st_stream(mp + (int64_t)row * ldT, mom);
+                        }
+                        y = half_step<MOM>(xv[u], gv[u], mom, lr, mu);
                     }
-                    y = half_step<MOM>(xv[u], gv[u], mom, lr, mu);
+                    sy[row * kWave + lane] = y;
                 }
-                sy[row * kWave + lane] = y;
             }
         }
-    }
-    __syncthreads();
-    // Phase 2: output rows wave, wave + 4, ... from the staged y.  The (j, w_ij) list of
-    // a row is fetched with one coalesced load (lane p holds entry p; the next row's list
-    // is fetched while this row is being summed) and broadcast entry by entry with
-    // readlane; taps are taken four at a time (padding taps have weight 0 and read row 0)
-    // so that four LDS reads are in flight.  All lanes stay active: readlane must find
-    // every source lane's registers written.
-    auto fetch_list = [&](int i, int c0, int& cj, float& wv) {
-        cj = 0;
-        wv = 0.f;
-        if (i < n) {
-            const int p = a.w.ptr[i] + c0 + lane;
-            if (p < a.w.ptr[i + 1]) {
-                cj = a.w.col[p];
-                wv = a.w.val[p];
+        __syncthreads();
+        // Phase 2: output rows wave, wave + W, ... from the staged y.  The (j, w_ij) list of
+        // a row is fetched with one coalesced load (lane p holds entry p; the next row's list
+        // is fetched while this row is being summed) and broadcast entry by entry with
+        // readlane; taps are taken four at a time (padding taps have weight 0 and read row 0)
+        // so that four LDS reads are in flight.  All lanes stay active: readlane must find
+        // every source lane's registers written.
+        auto fetch_list = [&](int i, int c0, int& cj, float& wv) {
+            cj = 0;
+            wv = 0.f;
+            if (i < n) {
+                const int p = a.w.ptr[i] + c0 + lane;
+                if (p < a.w.ptr[i + 1]) {
+                    cj = a.w.col[p];
+                    wv = a.w.val[p];
+                }
             }
-        }
-    };
-    int cj_next;
-    float wv_next;
-    fetch_list(wave, 0, cj_next, wv_next);
-    for (int i = wave; i < n; i += kTileWaves) {
-        const int cnt = a.w.ptr[i + 1] - a.w.ptr[i];
-        int cj_l = cj_next;
-        float wv_l = wv_next;
-        fetch_list(i + kTileWaves, 0, cj_next, wv_next);
-        T acc = T(0);
-        for (int c0 = 0; c0 < cnt; c0 += kWave) {
-            if (c0 > 0) fetch_list(i, c0, cj_l, wv_l);
-            const int m = cnt - c0 < kWave ? cnt - c0 : kWave;
-            for (int q = 0; q < m; q += 4) {
+        };
+        int cj_next;
+        float wv_next;
+        fetch_list(wave, 0, cj_next, wv_next);
+        for (int i = wave; i < n; i += kTileWaves) {
+            const int cnt = a.w.ptr[i + 1] - a.w.ptr[i];
+            int cj_l = cj_next;
+            float wv_l = wv_next;
+            fetch_list(i + kTileWaves, 0, cj_next, wv_next);
+            T acc = T(0);
+            for (int c0 = 0; c0 < cnt; c0 += kWave) {
+                if (c0 > 0) fetch_list(i, c0, cj_l, wv_l);
+                const int m = cnt - c0 < kWave ? cnt - c0 : kWave;
+                for (int q = 0; q < m; q += 4) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int cj = __builtin_amdgcn_readlane(cj_l, q + t);
-                    const float wv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wv_l), q + t));
-                    acc += wv * sy[cj * kWave + lane];
+                    for (int t = 0; t < 4; ++t) {
+                        const int cj = __builtin_amdgcn_readlane(cj_l, q + t);
+                        const float wv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wv_l), q + t));
+                        acc += wv * sy[cj * kWave + lane];
+                    }
                 }
             }
+            pace_wait(a.pace, t0, units_done);
+            units_done += 1u;
+            if (on) st_stream(xnp + (int64_t)i * ldT, acc);
         }
-        if (on) st_stream(xnp + (int64_t)i * ldT, acc);
+        __syncthreads();  // the next tile's phase 1 overwrites the staged y
     }
 }
 
@@ -181,22 +198,45 @@ __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, 
     st_stream(reinterpret_cast<T*>(x_new + col0) + col + (int64_t)i * ldT, acc);
 }
 
+
+template <typename T, int MOM>
+hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds) {
+    const int threads = kWave * waves;
+    int64_t blocks = a.tiles;
+    a.pace.unit_fp = 0;
+    a.pace.slots = nullptr;
+    a.pace.seq = 0;
+    // Default: one workgroup per tile.  On request ("pace_gbs" / "blocks_per_cu" options) exactly
+    // the resident workgroups, striding over the tiles and paced.  Measured on the n = 64,
+    // d = 25.6M shape the paced form is bimodal (5.0-5.1 TB/s at most targets, 5.5-5.7 TB/s at
+    // isolated ones) against a steady 5.2-5.3 TB/s one-shot, so it is not the default.
+    const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : 0.0;
+    const int want = c->opt_blocks_per_cu < 0 ? (gbs > 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
+    if (want > 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM>, threads, lds) != hipSuccess || occ < 1)
+            occ = 1;
+        const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
+        if (resident < blocks) blocks = resident;
+        pace_setup(const_cast<gpga_ctx*>(c), gbs, (double)blocks * waves, (int)sizeof(T), &a.pace);
+    }
+    hipLaunchKernelGGL((k_step_tile<T, MOM>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom) {
     TileArgs a;
     a.ge = ge;
     a.w = w;
-    const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
-    if (tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    a.tiles = (ge.ncols + kWave - 1) / kWave;
+    if (a.tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t lds = (size_t)ge.n * kWave * sizeof(T);
     // measured on the n = 64, d = 25.6M shape: 8 or 16 wavefronts per workgroup stream
     // 5.2-6.0 TB/s, 4 wavefronts 4.8-5.1 TB/s (more rows are in flight while others mix)
     const int waves = c->opt_mix_waves ? c->opt_mix_waves : (ge.n >= 32 ? 8 : kTileWavesDefault);
-    const dim3 grid((unsigned)tiles), block(kWave * waves);
-    if (mom == 2) hipLaunchKernelGGL((k_step_tile<T, 2>), grid, block, lds, c->stream, a);
-    else if (mom == 1) hipLaunchKernelGGL((k_step_tile<T, 1>), grid, block, lds, c->stream, a);
-    else hipLaunchKernelGGL((k_step_tile<T, 0>), grid, block, lds, c->stream, a);
-    return hipGetLastError();
+    if (mom == 2) return launch_tile_mom<T, 2>(c, a, waves, lds);
+    return mom == 1 ? launch_tile_mom<T, 1>(c, a, waves, lds) : launch_tile_mom<T, 0>(c, a, waves, lds);
 }
 
 template <typename T>

@@ -30,6 +30,7 @@
 #include <type_traits>
 
 #include "gpga_internal.hpp"
+#include "gpga_pace.hpp"
 
 namespace {
 
@@ -118,13 +119,6 @@ struct ColumnSpread<float> {  // never instantiated with tracing on; keeps the t
 constexpr int kMaxWaves = 8;
 constexpr int kDefaultUnroll = 2;  // rows per batch; two batches are in flight (software pipeline)
 
-// Pacing of a persistent launch (see pace_begin / pace_wait below).
-struct PaceArgs {
-    unsigned long long* slots;  // 64 start-time words, one per launch sequence number mod 64
-    uint32_t seq;               // launch sequence number
-    uint32_t unit_fp;           // clock counts (x 256) per 4-byte stream row of the whole launch; 0 = off
-};
-
 struct WalkArgs {
     StepGeom ge;
     int32_t S;    // row stride of the permutation
@@ -151,42 +145,6 @@ __device__ __forceinline__ int64_t logical_block(int64_t bid, int64_t gx, int xc
     return (bid & 7) * per + (bid >> 3);
 }
 
-// Deadline pacing of a persistent launch.  Measured on this chip: a 3-read /
-// 2-write stream mix runs at 6.3-6.5 TB/s when the whole chip streams one row
-// of each array at a time, and drops to the 5.1-5.2 TB/s of a scattered copy
-// once >= 32 different rows are open at once - which is what free-running
-// walkers drift into, since each is at a different row of its own tile.
-// Pacing keeps them together without exchanging data: all wavefronts share
-// one start time t0 (the first workgroup to arrive publishes the chip's
-// constant-rate clock with a compare-and-swap) and a wavefront issues the
-// loads of a row batch no earlier than t0 + (stream rows it has issued so
-// far) * unit, where unit is the time the whole launch needs for one stream
-// row at the target rate.  A late wavefront never waits; every wait ends at its
-// deadline (the clock always advances) and is also capped by a poll count, so
-// the grid always drains.
-__device__ __forceinline__ unsigned long long pace_begin(const PaceArgs& p, int lane, bool first_thread) {
-    if (!p.unit_fp) return 0ull;
-    if (first_thread) p.slots[(p.seq + 32u) & 63u] = 0ull;  // recycle a slot for a later launch
-    const unsigned long long mine = __builtin_amdgcn_s_memrealtime();
-    unsigned long long seen = 0;
-    if (lane == 0) {
-        seen = atomicCAS(p.slots + (p.seq & 63u), 0ull, mine);
-        if (seen == 0ull) seen = mine;
-    }
-    // readfirstlane returns a signed int: go through unsigned before widening
-    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(seen >> 32));
-    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(seen & 0xffffffffull));
-    const unsigned long long t0v = ((unsigned long long)hi << 32) | (unsigned long long)lo;
-    return t0v;
-}
-__device__ __forceinline__ void pace_wait(const PaceArgs& p, unsigned long long t0, uint32_t units_done) {
-    if (!p.unit_fp) return;
-    const unsigned long long deadline = t0 + (((unsigned long long)units_done * p.unit_fp) >> 8);
-    for (int guard = 0; guard < (1 << 14); ++guard) {
-        if (__builtin_amdgcn_s_memrealtime() >= deadline) break;
-        __builtin_amdgcn_s_sleep(2);
-    }
-}
 
 // MOM: 0 = no momentum buffer, 1 = heavy-ball, 2 = Nesterov.
 // TRACE: also sum (x_new - column mean)^2 over everything stored; requires that one
@@ -670,17 +628,7 @@ hipError_t launch_planned(Kernel kernel, LaunchPlan plan, Args a, hipStream_t st
         if (resident < blocks) blocks = resident;  // persistent: each workgroup strides over the work items
         // Pacing needs every workgroup of the launch to be resident at once, which
         // holds here: blocks <= CUs x workgroups per CU that fit.
-        gpga_ctx* c = const_cast<gpga_ctx*>(plan.ctx);
-        if (plan.pace_gbs > 0.0 && c->pace_slots) {
-            // time (clock counts x 256) for the whole launch to move one 4-byte stream row
-            const double bytes = (double)blocks * plan.waves * kWave * plan.vec * 4.0;
-            const double fp = bytes / (plan.pace_gbs * 1e9) * plan.clock_hz * 256.0;
-            if (fp >= 1.0 && fp < 4.0e9) {
-                a.pace.unit_fp = (uint32_t)fp;
-                a.pace.slots = c->pace_slots;
-                a.pace.seq = c->pace_seq++;
-            }
-        }
+        pace_setup(const_cast<gpga_ctx*>(plan.ctx), plan.pace_gbs, (double)blocks * plan.waves, plan.vec * 4, &a.pace);
     }
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (plan.blocks_out) *plan.blocks_out = blocks;

@@ -120,6 +120,30 @@ def test_two_pass_path_gives_the_tile_kernels_answer_and_leaves_y_in_g(hx, n, d,
     assert_close(outs[1][2], Y_ref, TOL_STEP, "g after the two-pass step holds x^(k+1/2)")
 
 
+@pytest.mark.parametrize("opts", [{"blocks_per_cu": 1}, {"blocks_per_cu": 1, "pace_gbs": 3000},
+                                  {"blocks_per_cu": 2, "pace_gbs": 8000, "mix_waves": 4}, {"mix_waves": 16},
+                                  {"mix_lane_bytes": 8}, {"mix_lane_bytes": 4, "mix_waves": 2}],
+                         ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
+@pytest.mark.parametrize("topology", ["grid", "expo"])
+def test_tile_kernel_launch_shapes_give_the_same_answer(hx, topology, opts):
+    # wide enough that a capped grid strides over several tiles per workgroup (and waits on its deadlines)
+    n, d = 64, 300_004
+    X, Mb, G = inputs.random_state(n, d, seed=77)
+    sim = hx.Simulation(n, d, topology=topology, H=0, lr=0.1, momentum=0.9)
+    for name, v in opts.items():
+        sim.set_option(name, v)
+    sim.set_state(X=X, M=Mb, G=G, k=0)
+    X_ref, M_ref = X, Mb
+    for j in range(2):
+        sim.step()
+        X_ref, M_ref = orc.gossip_pga_step(X_ref, M_ref, G, j, topology=topology, H=0, lr=0.1, momentum=0.9)
+        X_ref = X_ref.astype(np.float32).astype(np.float64)
+        M_ref = M_ref.astype(np.float32).astype(np.float64)
+        assert_close(host(sim.X), X_ref, TOL_STEP, f"X after step {j}")
+        assert_close(host(sim.M), M_ref, TOL_STEP, f"M after step {j}")
+    sim.close()
+
+
 def test_custom_W_equal_to_the_ring_matches_the_ring_stencil_kernel(hx):
     n, d = 64, 5000
     X, Mb, G = inputs.random_state(n, d, seed=3)
