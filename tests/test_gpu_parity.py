@@ -354,20 +354,24 @@ def test_cfg2_shapes_with_normalised_features_free_running(hx):
     sim.close()
 
 
-def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None):
+def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None, nesterov=False, H=None):
     """Column-separable workloads (synthetic gradients): the oracle runs the whole
     trajectory on column slabs, the GPU runs the full array; the slab columns are
     compared after every step."""
     c = inputs.CONFIGS[cfg_name]
     n, d = c["n"], c["d"]
     T = c["T"] if T is None else T
+    c = dict(c, H=c["H"] if H is None else H)
     cols = inputs.slab_columns(d, n_slabs, width)
     sim = hx.Simulation(n, d, topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"])
+    if nesterov:
+        sim.set_nesterov(True)
     for name, v in (opts or {}).items():
         sim.set_option(name, v)
     sim.problem_synthetic(c["seed"], c["grad_var"])
     cols_d = torch.as_tensor(cols, device=sim.device)
-    ref = orc.GossipPGA(n, len(cols), topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"], storage="f32")
+    ref = orc.GossipPGA(n, len(cols), topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"],
+                        nesterov=nesterov, storage="f32")
     worst = 0.0
     for k in range(T):
         sim.local_grad()
@@ -395,6 +399,24 @@ def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None):
 @pytest.mark.parametrize("topology", ["ring", "expo1"])
 def test_cfg3_resnet50_sized_slabs(hx, topology):
     _slab_trajectory(hx, "cfg3", topology, n_slabs=32, width=1024)
+
+
+@pytest.mark.parametrize("topology,nesterov", [("grid", False), ("expo", True), ("ring", True)])
+def test_cfg3_sized_slabs_sparse_W_and_nesterov(hx, topology, nesterov):
+    # the widened variants at the benchmark's full size: LDS-tile kernel (grid, static exponential
+    # graph) and Nesterov momentum, two averaging periods
+    _slab_trajectory(hx, "cfg3", topology, n_slabs=32, width=1024, T=17, nesterov=nesterov, H=8)
+
+
+def test_cfg5_sized_slabs_sparse_W_two_pass(hx):
+    # n = 1024 rows: update pass writing y over g, then the sparse product (synthetic gradients
+    # on the cfg5 shape so that the oracle can follow column slabs)
+    c = dict(inputs.CONFIGS["cfg5"], problem="synthetic", grad_var=1e-3)
+    inputs.CONFIGS["cfg5_synth"] = c
+    try:
+        _slab_trajectory(hx, "cfg5_synth", "grid", n_slabs=16, width=256, T=10, H=8)
+    finally:
+        del inputs.CONFIGS["cfg5_synth"]
 
 
 def test_cfg4_bert_base_sized_slabs(hx):
