@@ -771,6 +771,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "pace_gbs")) {
         if (value < -1 || value > 16000) return fail(c, GPGA_EINVAL, "pace_gbs must be -1 (automatic), 0 (off) or a rate up to 16000 GB/s");
         c->opt_pace_gbs = (int)value;
+    } else if (!strcmp(name, "cycle_kernel")) {
+        if (value < -1 || value > 1) return fail(c, GPGA_EINVAL, "cycle_kernel must be -1 (automatic), 0 or 1");
+        c->opt_cycle_kernel = (int)value;
     } else if (!strcmp(name, "pace_min_cycle")) {
         if (value < 0 || value > (1 << 24)) return fail(c, GPGA_EINVAL, "pace_min_cycle must be 0 (automatic) or a row count");
         c->opt_pace_min_cycle = (int)value;

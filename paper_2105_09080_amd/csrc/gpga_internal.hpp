@@ -83,6 +83,7 @@ struct gpga_ctx {
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
     int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
+    int opt_cycle_kernel = -1;   // whole-cycle kernel for one-peer cycles of 2 / 4 rows: -1 automatic, 0 never, 1 always
     int opt_pace_min_cycle = 0;  // shortest row cycle that is paced (0 = automatic)
     uint32_t pace_seq = 0;   // sequence number of paced launches
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code

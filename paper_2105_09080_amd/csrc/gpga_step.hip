@@ -363,6 +363,99 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     }
 }
 
+// One-peer steps whose cycles are short (2 or 4 rows: offsets n/2 and n/4).  A batch is one
+// whole cycle: its L rows are loaded, turned into y, and every row's pair average
+// (y_j + y_{j+1 mod L}) / 2 is stored; nothing is carried from one batch to the next, so the
+// loop over the C cycles of a column tile is a plain software pipeline (the next cycle's
+// loads are issued ahead of this cycle's stores) and the launch can be persistent and
+// paced like the long walks: the whole chip then streams the same L rows at a time.
+struct CycleArgs {
+    StepGeom ge;
+    int32_t S;   // row offset of the peer
+    int32_t C;   // number of cycles
+    int64_t gx;  // tile groups (one column tile per wavefront)
+    PaceArgs pace;
+};
+
+template <int MOM, int L>
+__global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArgs a) {
+    typedef v4f T;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int waves = blockDim.x >> 6;
+    const int n = a.ge.n;
+    const int S = a.S;
+    const int64_t ldT = a.ge.ld / 4;
+    const float lr = a.ge.lr, mu = a.ge.mu;
+    constexpr uint32_t kRowUnits = MOM ? 5u : 3u;
+    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    uint32_t units_done = 0;
+
+    for (int64_t w = blockIdx.x; w < a.gx; w += gridDim.x) {
+        const int64_t col = (w * waves + wave) * kWave + lane;
+        if (col >= a.ge.ncols) continue;
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+
+        struct Batch {
+            T xv[L], mv[L], gv[L];
+            int rw[L];
+        };
+        auto load_cycle = [&](Batch& b, int cyc) {
+            pace_wait(a.pace, t0, units_done);
+            units_done += L * kRowUnits;
+            int row = cyc;
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                b.rw[j] = row;
+                const int64_t off = (int64_t)row * ldT;
+                b.xv[j] = ld_stream(xp + off);
+                if (MOM) b.mv[j] = ld_stream(mp + off);
+                b.gv[j] = ld_stream(gp + off);
+                row += S;
+                if (row >= n) row -= n;
+            }
+        };
+        auto store_cycle = [&](const Batch& b) {
+            T y[L];
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                T mom = b.gv[j];
+                if (MOM) {
+                    mom = mu * b.mv[j] + b.gv[j];
+                    st_stream(mp + (int64_t)b.rw[j] * ldT, mom);
+                }
+                y[j] = half_step<MOM>(b.xv[j], b.gv[j], mom, lr, mu);
+            }
+#pragma unroll
+            for (int j = 0; j < L; ++j) st_stream(xnp + (int64_t)b.rw[j] * ldT, (y[j] + y[(j + 1) % L]) * 0.5f);
+        };
+        Batch A, B;
+        load_cycle(A, 0);
+        int c = 0;
+        for (; c + 3 <= a.C; c += 2) {
+            load_cycle(B, c + 1);
+            __builtin_amdgcn_sched_barrier(0);  // keep the issue order: loads, then stores
+            store_cycle(A);
+            __builtin_amdgcn_sched_barrier(0);
+            load_cycle(A, c + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            store_cycle(B);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (a.C - c == 2) {
+            load_cycle(B, c + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            store_cycle(A);
+            store_cycle(B);
+        } else {
+            store_cycle(A);
+        }
+    }
+}
+
 struct GlobalArgs {
     StepGeom ge;
     int32_t RL;   // lanes of a wave spread over rows (1, 2, 4)
@@ -688,6 +781,7 @@ constexpr int64_t kPacedWaves = 2048;
 constexpr int kAutoBlocksPerCu = 4;
 constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
 constexpr double kAutoPaceGbsShort = 6000.0;   // walks over cycles of 8 rows
+constexpr double kAutoPaceGbsCycles = 6000.0;  // whole-cycle batches (cycles of 2 or 4 rows)
 constexpr double kAutoPaceGbsGlobal = 6300.0;  // same stream mix as the walk once the mean rows are deferred
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
@@ -726,6 +820,29 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     }
     const int waves = c->opt_waves ? c->opt_waves : 4;
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
+
+    // One-peer offsets n/2 and n/4 on large problems: whole-cycle batches, persistent and paced.
+    if (mode == MODE_PEER && vec == 4 && (a.L == 2 || a.L == 4) && !c->opt_row_split && c->opt_cycle_kernel != 0 &&
+        (tiles >= kPacedWaves || c->opt_cycle_kernel == 1)) {
+        CycleArgs ca;
+        ca.ge = ge;
+        ca.S = S;
+        ca.C = a.C;
+        ca.gx = (tiles + waves - 1) / waves;
+        // measured on the n = 64, d = 25.6M shape: cycles of 2 rows 6.00 TB/s at a 6.15 TB/s target
+        // (one-shot walk 5.80), cycles of 4 rows 5.65 TB/s at 5.8-6.0 (one-shot walk 5.51)
+        LaunchPlan plan = make_plan(c, ca.gx, waves, vec, true, a.L == 2 ? 6150.0 : kAutoPaceGbsCycles);
+        if (c->opt_blocks_per_cu < 0 && plan.bpc == 0) plan.bpc = kAutoBlocksPerCu;  // forced on a small problem
+        const int momk = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
+        if (a.L == 2) {
+            if (momk == 2) return launch_planned(k_step_cycles<2, 2>, plan, ca, c->stream);
+            return momk ? launch_planned(k_step_cycles<1, 2>, plan, ca, c->stream)
+                        : launch_planned(k_step_cycles<0, 2>, plan, ca, c->stream);
+        }
+        if (momk == 2) return launch_planned(k_step_cycles<2, 4>, plan, ca, c->stream);
+        return momk ? launch_planned(k_step_cycles<1, 4>, plan, ca, c->stream)
+                    : launch_planned(k_step_cycles<0, 4>, plan, ca, c->stream);
+    }
 
     int Q = 1;
     if (mode != MODE_SELF && mode != MODE_INPLACE) {

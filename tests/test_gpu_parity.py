@@ -155,6 +155,36 @@ def test_persistent_paced_launch_matches_oracle(hx, topology, k, H, opts):
     sim.close()
 
 
+@pytest.mark.parametrize("n,d,k,momentum,opts", [
+    (64, 300_004, 4, 0.9, {"cycle_kernel": 1}),                       # offset 16: cycles of 4 rows
+    (64, 300_004, 5, 0.9, {"cycle_kernel": 1}),                       # offset 32: cycles of 2 rows
+    (64, 300_004, 5, 0.0, {"cycle_kernel": 1, "pace_gbs": 2000}),
+    (64, 300_004, 4, 0.9, {"cycle_kernel": 1, "blocks_per_cu": 1, "waves": 2, "pace_gbs": 8000}),
+    (1024, 4100, 9, 0.9, {"cycle_kernel": 1}),                        # offset 512
+    (1024, 4100, 8, 0.9, {"cycle_kernel": 1, "blocks_per_cu": 0}),    # offset 256, one-shot launch
+    (2, 1000, 0, 0.9, {"cycle_kernel": 1}),                           # n = 2: one cycle of two rows
+    (4, 1000, 0, 0.5, {"cycle_kernel": 1}),                           # offset 1 on n = 4: one cycle of four rows
+    (8, 999, 2, 0.9, {"cycle_kernel": 1}),                            # ragged d: the scalar tail takes the walk
+    (64, 300_004, 4, 0.9, {"cycle_kernel": 0}),                       # switched off: the walk kernel
+])
+def test_whole_cycle_kernel_for_short_one_peer_cycles(hx, n, d, k, momentum, opts):
+    X, Mb, G = inputs.random_state(n, d, seed=500 + n + k)
+    for nesterov in ((False, True) if momentum else (False,)):
+        sim = hx.Simulation(n, d, topology="expo1", H=0, lr=0.1, momentum=momentum)
+        if nesterov:
+            sim.set_nesterov(True)
+        for name, v in opts.items():
+            sim.set_option(name, v)
+        sim.set_state(X=X, M=Mb, G=G, k=k)
+        sim.step()
+        X_ref, M_ref = orc.gossip_pga_step(X, Mb if momentum else np.zeros_like(Mb), G, k, topology="expo1", H=0,
+                                           lr=0.1, momentum=momentum, nesterov=nesterov)
+        assert_close(host(sim.X), X_ref, TOL_STEP, "X")
+        if momentum:
+            assert_close(host(sim.M), M_ref, TOL_STEP, "M")
+        sim.close()
+
+
 def test_padding_columns_and_inputs_are_untouched(hx):
     n, d, ld = 8, 1001, 1008
     sim = hx.Simulation(n, d, topology="ring", H=0, lr=0.1, momentum=0.9, ld=ld)
