@@ -70,7 +70,7 @@ def parse_args():
     ap.add_argument("--config", default="cfg3", help="primary workload: cfg3 or cfg4 (or cfg5 step-only)")
     ap.add_argument("--topology", default=None,
                     help="ring, expo1, grid, expo, none or full (default: first listed for the workload)")
-    ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1",
+    ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1,cfg5:ring",
                     help="comma list of extra workload:topology pairs measured after the primary ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0,
