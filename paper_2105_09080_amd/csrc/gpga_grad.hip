@@ -39,8 +39,9 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
         const uint64_t p0 = (uint64_t)kPhiloxM0 * c0, p1 = (uint64_t)kPhiloxM1 * c2;
         const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
         const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
-        const uint32_t n0 = hi1 ^ c1 ^ k0;
-        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        // three-input xor in one instruction (v_bitop3_b32, truth table 0x96 = a ^ b ^ c)
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32(hi1, c1, k0, 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32(hi0, c3, k1, 0x96);
         c0 = n0;
         c1 = lo1;
         c2 = n2;
@@ -51,9 +52,13 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
     return {c0, c1, c2, c3};
 }
 
-// 32 random bits -> uniform in (0,1), exactly representable in fp32.
+// 32 random bits -> uniform in (0,1), exactly representable in fp32: u = ((r >> 9) + 0.5) * 2^-23.
+// Built without an integer-to-float conversion: the 23 bits become the mantissa of a float in
+// [1, 2) (one funnel shift puts the exponent 0x7F above them), and subtracting 1 - 2^-24 leaves
+// (k + 0.5) * 2^-23 exactly (it has at most 24 significant bits, so the subtraction does not round).
 __device__ __forceinline__ float uniform23(uint32_t r) {
-    return ((float)(r >> 9) + 0.5f) * 0x1p-23f;
+    const uint32_t bits = __builtin_amdgcn_alignbit(0x7Fu, r, 9u);  // ({0x7F, r} >> 9) = 0x3F800000 | (r >> 9)
+    return __uint_as_float(bits) - 0x1.fffffep-1f;
 }
 
 // Four standard normals for one column quad: Box-Muller on (u0,u1) and (u2,u3).
