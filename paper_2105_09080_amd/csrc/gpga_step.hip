@@ -129,6 +129,7 @@ struct WalkArgs {
     int32_t xcd;  // remap tile groups so that an XCD sees contiguous tiles
     int64_t gx;   // tile groups
     int64_t gy;   // walker groups; work items = gx * gy, tile group fastest
+    int32_t cpi;  // cycles per work item (1, or all C cycles when the consensus sums ride along)
     double* spread_partials;  // TRACE kernels: one sum of squared deviations per workgroup
     PaceArgs pace;
 };
@@ -184,7 +185,10 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     for (int64_t w = blockIdx.x; w < work; w += gridDim.x) {
         const int by = (int)(w / a.gx);
         const int64_t bx = w - (int64_t)by * a.gx;
-        const int walker = by * wpb + walk_l;
+        // cpi > 1 (tracing one-peer steps): this work item takes all cycles of its column tile one
+        // after the other, so that the lane stores - and sums - whole columns
+        for (int cc = 0; cc < a.cpi; ++cc) {
+        const int walker = (by * a.cpi + cc) * wpb + walk_l;
         const bool walker_on = walker < a.C * a.Q;
         const int cyc = walker / a.Q;
         const int seg = walker - cyc * a.Q;
@@ -262,7 +266,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 units_done += (len >= 2 ? 2u : 1u) * kRowUnits;
                 load_row(x0, m0, g0, r0);
                 if (len >= 2) load_row(x1, m1, g1, r1);
-                if (TRACE) spread.reset(x0);
+                if (TRACE && cc == 0) spread.reset(x0);
                 yf = y_of(x0, m0, g0, r0);
                 if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r0 * ldT, yf);
                 // in place: through a pointer derived from gp, the one this element was read with
@@ -345,8 +349,9 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             } else {  // MODE_PEER: last row of the segment pairs with the next segment's first
                 put(row_prev, (pc + right) * 0.5f);
             }
-            if (TRACE) spread_acc += spread.sum_sq(1.0 / (double)n);
+            if (TRACE && cc == a.cpi - 1) spread_acc += spread.sum_sq(1.0 / (double)n);
         }
+        }  // cycles of this work item
     }
     if (TRACE) {
         // one partial per workgroup, summed in a fixed order
@@ -884,10 +889,18 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : kDefaultUnroll);
     const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     a.spread_partials = nullptr;
-    // the consensus sums can ride along when one walker stores whole columns
-    if (spread_partials && spread_count && vec == 4 && Q == 1 && a.C == 1 && (U == 1 || U == 2) &&
+    a.cpi = 1;
+    // the consensus sums can ride along when one walker stores whole columns: a single cycle, or
+    // (paced launches with one cycle per workgroup) all cycles of a tile taken in turn by one walker
+    const bool whole_columns = a.C == 1 || (wpb == 1 && plan.pace_gbs > 0.0 && plan.bpc > 0);
+    if (spread_partials && spread_count && vec == 4 && Q == 1 && whole_columns && (U == 1 || U == 2) &&
         (mode == MODE_RING || mode == MODE_PEER)) {
         LaunchPlan tp = plan;
+        if (a.C > 1) {
+            a.cpi = a.C;
+            a.gy = 1;
+            tp.work = a.gx;
+        }
         tp.blocks_out = spread_count;
         a.spread_partials = spread_partials;
         if (mom == 2) return launch_walk_trace<2>(mode, U, tp, c->stream, a);

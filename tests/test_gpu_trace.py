@@ -32,6 +32,8 @@ CASES = [
     (5, 1000, "expo1", 3, 0.9, 7, {}),                        # n odd: every one-peer offset is one cycle
     (64, 4100, "ring", 4, 0.9, 6, {}),                        # rows split over wavefronts: reduction pass
     (64, 300_004, "expo1", 0, 0.9, 7, {}),                    # several cycles: reduction pass
+    (64, 600_000, "expo1", 0, 0.9, 7, {"blocks_per_cu": 2, "pace_gbs": 4000}),   # paced: one walker takes all cycles
+    (64, 600_000, "expo1", 6, 0.9, 8, {"blocks_per_cu": 4, "pace_gbs": 9000, "unroll": 2}),
     (16, 1003, "ring", 5, 0.9, 6, {}),                        # ragged d: scalar tail -> reduction pass
     (20, 2000, "grid", 4, 0.9, 6, {}),                        # sparse W
     (12, 500, "none", 3, 0.5, 5, {}),
