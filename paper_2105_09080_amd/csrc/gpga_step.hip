@@ -379,12 +379,16 @@ struct CycleArgs {
     int32_t S;   // row offset of the peer
     int32_t C;   // number of cycles
     int64_t gx;  // tile groups (one column tile per wavefront)
+    double* spread_partials;  // TRACE kernels: one sum of squared deviations per workgroup
     PaceArgs pace;
 };
 
-template <int MOM, int L>
+template <int MOM, int L, bool TRACE = false>
 __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArgs a) {
     typedef v4f T;
+    __shared__ double s_spread[kMaxWaves];
+    ColumnSpread<T> spread;
+    double spread_acc = 0.0;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int waves = blockDim.x >> 6;
@@ -399,6 +403,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArg
     for (int64_t w = blockIdx.x; w < a.gx; w += gridDim.x) {
         const int64_t col = (w * waves + wave) * kWave + lane;
         if (col >= a.ge.ncols) continue;
+        if (TRACE) spread.reset(reinterpret_cast<const T*>(a.ge.x + a.ge.col0)[col]);  // row 0 of the old iterate
         const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
         const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
         T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
@@ -435,7 +440,11 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArg
                 y[j] = half_step<MOM>(b.xv[j], b.gv[j], mom, lr, mu);
             }
 #pragma unroll
-            for (int j = 0; j < L; ++j) st_stream(xnp + (int64_t)b.rw[j] * ldT, (y[j] + y[(j + 1) % L]) * 0.5f);
+            for (int j = 0; j < L; ++j) {
+                const T v = (y[j] + y[(j + 1) % L]) * 0.5f;
+                st_stream(xnp + (int64_t)b.rw[j] * ldT, v);
+                if (TRACE) spread.add(v);
+            }
         };
         Batch A, B;
         load_cycle(A, 0);
@@ -457,6 +466,19 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArg
             store_cycle(B);
         } else {
             store_cycle(A);
+        }
+        if (TRACE) spread_acc += spread.sum_sq(1.0 / (double)n);
+    }
+    if (TRACE) {
+        double v = spread_acc;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+        if (lane == 0) s_spread[wave] = v;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int w2 = 0; w2 < waves; ++w2) t += s_spread[w2];
+            a.spread_partials[blockIdx.x] = t;
         }
     }
 }
@@ -839,6 +861,19 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
         LaunchPlan plan = make_plan(c, ca.gx, waves, vec, true, a.L == 2 ? 6150.0 : kAutoPaceGbsCycles);
         if (c->opt_blocks_per_cu < 0 && plan.bpc == 0) plan.bpc = kAutoBlocksPerCu;  // forced on a small problem
         const int momk = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
+        ca.spread_partials = nullptr;
+        if (spread_partials && spread_count) {  // every lane stores whole columns: the consensus sums ride along
+            ca.spread_partials = spread_partials;
+            plan.blocks_out = spread_count;
+            if (a.L == 2) {
+                if (momk == 2) return launch_planned(k_step_cycles<2, 2, true>, plan, ca, c->stream);
+                return momk ? launch_planned(k_step_cycles<1, 2, true>, plan, ca, c->stream)
+                            : launch_planned(k_step_cycles<0, 2, true>, plan, ca, c->stream);
+            }
+            if (momk == 2) return launch_planned(k_step_cycles<2, 4, true>, plan, ca, c->stream);
+            return momk ? launch_planned(k_step_cycles<1, 4, true>, plan, ca, c->stream)
+                        : launch_planned(k_step_cycles<0, 4, true>, plan, ca, c->stream);
+        }
         if (a.L == 2) {
             if (momk == 2) return launch_planned(k_step_cycles<2, 2>, plan, ca, c->stream);
             return momk ? launch_planned(k_step_cycles<1, 2>, plan, ca, c->stream)
