@@ -807,7 +807,7 @@ constexpr int64_t kPacedWaves = 2048;
 // persistent and paced; everything else is a one-shot launch.
 constexpr int kAutoBlocksPerCu = 4;
 constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
-constexpr double kAutoPaceGbsShort = 6000.0;   // walks over cycles of 8 rows
+constexpr double kAutoPaceGbsShort = 6150.0;   // walks over cycles of 8 rows
 constexpr double kAutoPaceGbsCycles = 6000.0;  // whole-cycle batches (cycles of 2 or 4 rows)
 constexpr double kAutoPaceGbsGlobal = 6300.0;  // same stream mix as the walk once the mean rows are deferred
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
@@ -862,17 +862,15 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
         if (c->opt_blocks_per_cu < 0 && plan.bpc == 0) plan.bpc = kAutoBlocksPerCu;  // forced on a small problem
         const int momk = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
         ca.spread_partials = nullptr;
-        if (spread_partials && spread_count) {  // every lane stores whole columns: the consensus sums ride along
+        // every lane stores whole columns, so the consensus sums can ride along; only for cycles of two
+        // rows: with four-row batches the extra fp64 sums cost more (5.4 against 3.6 ms on n = 1024,
+        // d = 1M) than the separate reduction pass
+        if (spread_partials && spread_count && a.L == 2) {
             ca.spread_partials = spread_partials;
             plan.blocks_out = spread_count;
-            if (a.L == 2) {
-                if (momk == 2) return launch_planned(k_step_cycles<2, 2, true>, plan, ca, c->stream);
-                return momk ? launch_planned(k_step_cycles<1, 2, true>, plan, ca, c->stream)
-                            : launch_planned(k_step_cycles<0, 2, true>, plan, ca, c->stream);
-            }
-            if (momk == 2) return launch_planned(k_step_cycles<2, 4, true>, plan, ca, c->stream);
-            return momk ? launch_planned(k_step_cycles<1, 4, true>, plan, ca, c->stream)
-                        : launch_planned(k_step_cycles<0, 4, true>, plan, ca, c->stream);
+            if (momk == 2) return launch_planned(k_step_cycles<2, 2, true>, plan, ca, c->stream);
+            return momk ? launch_planned(k_step_cycles<1, 2, true>, plan, ca, c->stream)
+                        : launch_planned(k_step_cycles<0, 2, true>, plan, ca, c->stream);
         }
         if (a.L == 2) {
             if (momk == 2) return launch_planned(k_step_cycles<2, 2>, plan, ca, c->stream);
@@ -916,8 +914,8 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const bool uniform = (Q == 1) && (((int64_t)a.C * Q) % wpb == 0);
     // short cycles (< 8 rows per wavefront) already keep few rows open in a one-shot launch
     const int min_cycle = c->opt_pace_min_cycle > 0 ? c->opt_pace_min_cycle : 8;
-    // cycles of exactly 8 rows (one-peer offset n/8) peak at a slightly lower target: 5.98 TB/s
-    // at 6.0 against 5.68 TB/s at 6.3 on the n = 64, d = 25.6M shape
+    // cycles of exactly 8 rows (one-peer offset n/8) peak at a slightly lower target: 5.97 TB/s
+    // at 6.15-6.2 against 5.81 TB/s at 6.3 on the n = 64, d = 25.6M shape
     const double auto_gbs = a.L <= 8 ? kAutoPaceGbsShort : kAutoPaceGbsWalk;
     const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= min_cycle, auto_gbs);
     // paced wavefronts advance one row per batch (two rows in flight); free-running ones two
@@ -925,30 +923,32 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     a.spread_partials = nullptr;
     a.cpi = 1;
-    // the consensus sums can ride along when one walker stores whole columns: a single cycle, or
-    // (paced launches with one cycle per workgroup) all cycles of a tile taken in turn by one walker
-    const bool whole_columns = a.C == 1 || (wpb == 1 && plan.pace_gbs > 0.0 && plan.bpc > 0);
+    LaunchPlan lp = plan;
+    // Paced launches with one cycle per workgroup: a work item takes ALL cycles of its column tile
+    // in turn instead of one (measured 3.41 -> 3.33 ms on n = 1024, d = 1M); its lanes then store
+    // whole columns, as they do when there is a single cycle.
+    if (a.C > 1 && Q == 1 && wpb == 1 && plan.pace_gbs > 0.0 && plan.bpc > 0 && mode == MODE_PEER) {
+        a.cpi = a.C;
+        a.gy = 1;
+        lp.work = a.gx;
+    }
+    const bool whole_columns = a.C == 1 || a.cpi == a.C;
+    // the consensus sums can ride along when one walker stores whole columns
     if (spread_partials && spread_count && vec == 4 && Q == 1 && whole_columns && (U == 1 || U == 2) &&
         (mode == MODE_RING || mode == MODE_PEER)) {
-        LaunchPlan tp = plan;
-        if (a.C > 1) {
-            a.cpi = a.C;
-            a.gy = 1;
-            tp.work = a.gx;
-        }
-        tp.blocks_out = spread_count;
+        lp.blocks_out = spread_count;
         a.spread_partials = spread_partials;
-        if (mom == 2) return launch_walk_trace<2>(mode, U, tp, c->stream, a);
-        return mom ? launch_walk_trace<1>(mode, U, tp, c->stream, a) : launch_walk_trace<0>(mode, U, tp, c->stream, a);
+        if (mom == 2) return launch_walk_trace<2>(mode, U, lp, c->stream, a);
+        return mom ? launch_walk_trace<1>(mode, U, lp, c->stream, a) : launch_walk_trace<0>(mode, U, lp, c->stream, a);
     }
     if (vec == 4) {
-        if (mom == 2) return launch_walk_mode<v4f, 2>(mode, U, plan, c->stream, a);
-        return mom ? launch_walk_mode<v4f, 1>(mode, U, plan, c->stream, a)
-                   : launch_walk_mode<v4f, 0>(mode, U, plan, c->stream, a);
+        if (mom == 2) return launch_walk_mode<v4f, 2>(mode, U, lp, c->stream, a);
+        return mom ? launch_walk_mode<v4f, 1>(mode, U, lp, c->stream, a)
+                   : launch_walk_mode<v4f, 0>(mode, U, lp, c->stream, a);
     }
-    if (mom == 2) return launch_walk_mode<float, 2>(mode, U, plan, c->stream, a);
-    return mom ? launch_walk_mode<float, 1>(mode, U, plan, c->stream, a)
-               : launch_walk_mode<float, 0>(mode, U, plan, c->stream, a);
+    if (mom == 2) return launch_walk_mode<float, 2>(mode, U, lp, c->stream, a);
+    return mom ? launch_walk_mode<float, 1>(mode, U, lp, c->stream, a)
+               : launch_walk_mode<float, 0>(mode, U, lp, c->stream, a);
 }
 
 hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
