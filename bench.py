@@ -84,6 +84,10 @@ def parse_args():
                     help="instead of the benchmark, measure the chip's plain read / write / copy rates with the "
                          "library's streaming probe and the W = I fused step (3 reads : 2 writes, no mixing) on "
                          "the cfg3 shape; prints one JSON line")
+    ap.add_argument("--cfg5-sweep", type=int, default=0, metavar="T",
+                    help="instead of the benchmark, run cfg5 (n=1024, d=1M, virtual-feature logistic regression) "
+                         "for T steps over ring and one-peer topologies and H in {1, 8, 64, never}, recording the "
+                         "consensus distance after every step on the device; prints one JSON line per run")
     ap.add_argument("--opt", action="append", default=[], help="launch option name=value (repeatable)")
     return ap.parse_args()
 
@@ -223,6 +227,51 @@ def run_probe(reps=12):
     return {"probe": "MI355X streaming rates, 128-bit non-temporal accesses", "peak_gbs": HBM_PEAK_GBS, **out}
 
 
+def run_cfg5_sweep(T):
+    """cfg5 as stated: both topologies, H in {1, 8, 64, infinity}, consensus distance per step + throughput."""
+    import torch
+
+    from paper_2105_09080_amd import binding as B
+    from paper_2105_09080_amd import inputs
+    from paper_2105_09080_amd.harness import Simulation
+
+    c = inputs.CONFIGS["cfg5"]
+    n, d = c["n"], c["d"]
+    y = inputs.virtual_labels(n, c["M"], c["seed"])
+    idx_host = inputs.batch_indices(T, n, c["B"], c["M"], c["seed"])
+    for topology in c["topologies"]:
+        for H in c["H_sweep"]:
+            stream = torch.cuda.Stream()
+            sim = Simulation(n, d, topology=topology, H=H, lr=c["lr"], momentum=c["momentum"], stream=stream)
+            sim.problem_logreg_virtual(c["seed"], y, c["mu_var"])
+            idx = sim.upload_batches(idx_host)
+            trace = sim.attach_trace(T)
+            with torch.cuda.stream(stream):
+                sim.run(5, idx)                     # warm-up, then start again from x0 = 0
+            B.gpga_reset(sim.ctx, None)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            with torch.cuda.stream(stream):
+                sim.run(T, idx)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            tr = trace.cpu().numpy()
+            avg_steps = [k for k in range(T) if H > 0 and (k + 1) % H == 0]
+            other = [k for k in range(T) if k not in set(avg_steps)]
+            print(json.dumps({
+                "workload": f"cfg5: n={n} d={d} {topology} H={'inf' if H == 0 else H} T={T}",
+                "steps_per_s": T / dt, "ms_per_step": 1e3 * dt / T, "node_updates_per_s": n * T / dt,
+                "consensus_zero_after_every_average": bool(all(tr[k] == 0.0 for k in avg_steps)),
+                "consensus_max": float(tr.max()),
+                "consensus_mean_between_averages": float(tr[other].mean()) if other else 0.0,
+                "consensus_last_10": [float(v) for v in tr[-10:]],
+                "consensus_every_50th": [float(v) for v in tr[49::50]],
+            }), flush=True)
+            sim.close()
+            del sim
+            torch.cuda.empty_cache()
+
+
 def cpu_baseline(cfg_name, topology, budget_s=15.0):
     """The oracle as it stands on a column slab of the workload (the recursion is
     column-separable with synthetic gradients), scaled to the full width."""
@@ -272,6 +321,9 @@ def main():
         sys.exit(2)
     if args.probe:
         print(json.dumps(run_probe()))
+        return
+    if args.cfg5_sweep > 0:
+        run_cfg5_sweep(args.cfg5_sweep)
         return
     opts = {}
     for o in args.opt:
