@@ -180,8 +180,10 @@ gpga_status gpga_step(gpga_ctx* ctx);
  * nothing synchronises).  batch_table_dev: T x n x B int32 on the device, iteration
  * j of this call uses rows [j*n*B, (j+1)*n*B); NULL with B = 0 means full batches
  * (and is what the synthetic problem takes).  Stops at the first failing call and
- * returns its status; iterations before it stay enqueued.  Not for contexts with
- * adaptive averaging (ESTATE). */
+ * returns its status; iterations before it stay enqueued.  With adaptive averaging
+ * enabled (gpga_aga_enable) every iteration is a gpga_aga_step instead, the library
+ * evaluating the minibatch losses itself in the iterations that end in a global
+ * average (those synchronise, as gpga_aga_step does). */
 gpga_status gpga_run(gpga_ctx* ctx, int64_t T, const int32_t* batch_table_dev, int32_t B);
 
 /* Attach an arbitrary weight matrix W (Sec. 3: W >= 0, W 1 = 1, 1^T W = 1^T,

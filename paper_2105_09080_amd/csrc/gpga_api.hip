@@ -302,6 +302,7 @@ gpga_status gpga_destroy(gpga_ctx* c) {
     gpga_status s = GPGA_OK;
     if (c->bound && hipStreamSynchronize(c->stream) != hipSuccess) s = GPGA_EDEVICE;
     if (c->coef) (void)hipFree(c->coef);
+    if (c->aga_loss) (void)hipFree(c->aga_loss);
     if (c->partials) (void)hipFree(c->partials);
     if (c->pace_slots) (void)hipFree(c->pace_slots);
     free_csr_device(c);
@@ -640,10 +641,26 @@ gpga_status gpga_run(gpga_ctx* c, int64_t T, const int32_t* batch_table_dev, int
     if (!c) return GPGA_EINVAL;
     if (T < 0) return fail(c, GPGA_EINVAL, "T must be >= 0");
     if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
-    if (c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is enabled: iterate with gpga_aga_step");
     if (c->problem == PROB_NONE) return fail(c, GPGA_ESTATE, "no problem attached (gpga_problem_*)");
     DeviceGuard guard(c->device);
     const int64_t stride = batch_table_dev ? (int64_t)c->n * B : 0;
+    if (c->aga) {
+        // Algorithm 2: the minibatch losses are needed only in iterations that end in a global
+        // average, which the counter tells beforehand
+        gpga_status s = grow_f32(c, &c->aga_loss, &c->aga_loss_cap, (size_t)c->n);
+        if (s != GPGA_OK) return s;
+        for (int64_t j = 0; j < T; ++j) {
+            const int32_t* idx = batch_table_dev ? batch_table_dev + j * stride : nullptr;
+            if (c->aga_C + 1 == c->H) {
+                s = run_grad(c, idx, B, c->aga_loss);
+                if (s != GPGA_OK) return s;
+            }
+            s = run_grad(c, idx, B, nullptr);
+            if (s == GPGA_OK) s = gpga_aga_step(c, c->aga_loss);
+            if (s != GPGA_OK) return s;
+        }
+        return GPGA_OK;
+    }
     for (int64_t j = 0; j < T; ++j) {
         gpga_status s = run_grad(c, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, nullptr);
         if (s != GPGA_OK) return s;

@@ -111,6 +111,8 @@ struct gpga_ctx {
     bool aga = false;
     int64_t aga_H_init = 0, aga_warmup = 0, aga_H_max = 0, aga_C = 0;
     double aga_F_init = 0.0;
+    float* aga_loss = nullptr;  // n minibatch losses (library-owned; used by gpga_run)
+    size_t aga_loss_cap = 0;
 
     char err[256] = {0};
 };

@@ -90,8 +90,31 @@ def test_run_equals_stepping_one_iteration_at_a_time(hx, problem):
     with pytest.raises(B.GpgaError) as e:
         B.gpga_run(b_.ctx, -1, None, 0)
     assert e.value.status == B.GPGA_EINVAL
-    b_.aga_enable(2, 0, 8)
-    with pytest.raises(B.GpgaError) as e:
-        b_.run(1, idx_b)
-    assert e.value.status == B.GPGA_ESTATE
+    a.close(), b_.close()
+
+
+def test_run_with_adaptive_averaging_equals_explicit_aga_steps(hx):
+    n, d, M, Bsz, T = 16, 512, 64, 8, 60
+    feat, y, _ = inputs.logreg_problem(n, d, M, seed=21)
+    feat = (feat / np.sqrt(d)).astype(np.float32)
+    idx = inputs.batch_indices(T, n, Bsz, M, seed=21)
+    sims = []
+    for _ in range(2):
+        sim = hx.Simulation(n, d, topology="expo1", H=0, lr=0.5, momentum=0.9)
+        sim.problem_logreg(feat, y)
+        sim.aga_enable(2, 8, 12)
+        sims.append((sim, sim.upload_batches(idx)))
+    (a, idx_a), (b_, idx_b) = sims
+    periods = []
+    for k in range(T):
+        loss = a.local_loss(idx_a[k])
+        a.local_grad(idx_a[k])
+        a.aga_step(loss)
+        periods.append(a.period)
+    b_.run(25, idx_b)
+    b_.run(T - 25, idx_b[25:])
+    torch.cuda.synchronize()
+    assert b_.k == T and b_.period == periods[-1]
+    assert len(set(periods)) >= 2                      # the period did adapt along the way
+    assert torch.equal(a.X, b_.X) and torch.equal(a.M, b_.M)
     a.close(), b_.close()
