@@ -368,7 +368,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     }
 }
 
-// One-peer steps whose cycles are short (2 or 4 rows: offsets n/2 and n/4).  A batch is one
+// One-peer steps whose cycles are short (instantiated for 2 rows: offset n/2).  A batch is one
 // whole cycle: its L rows are loaded, turned into y, and every row's pair average
 // (y_j + y_{j+1 mod L}) / 2 is stored; nothing is carried from one batch to the next, so the
 // loop over the C cycles of a column tile is a plain software pipeline (the next cycle's
@@ -808,7 +808,8 @@ constexpr int64_t kPacedWaves = 2048;
 constexpr int kAutoBlocksPerCu = 4;
 constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
 constexpr double kAutoPaceGbsShort = 6150.0;   // walks over cycles of 8 rows
-constexpr double kAutoPaceGbsCycles = 6000.0;  // whole-cycle batches (cycles of 2 or 4 rows)
+constexpr double kAutoPaceGbsCycles = 6150.0;  // whole-cycle batches (cycles of 2 rows)
+constexpr double kAutoPaceGbsFour = 5950.0;    // walks over cycles of 4 rows
 constexpr double kAutoPaceGbsGlobal = 6300.0;  // same stream mix as the walk once the mean rows are deferred
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
@@ -848,38 +849,30 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const int waves = c->opt_waves ? c->opt_waves : 4;
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
 
-    // One-peer offsets n/2 and n/4 on large problems: whole-cycle batches, persistent and paced.
-    if (mode == MODE_PEER && vec == 4 && (a.L == 2 || a.L == 4) && !c->opt_row_split && c->opt_cycle_kernel != 0 &&
+    // One-peer offset n/2 on large problems (cycles of two rows): whole-cycle batches, persistent and
+    // paced.  Measured on the n = 64, d = 25.6M shape: 6.00 TB/s at a 6.15 TB/s target against 5.80
+    // for the one-shot walk.  (Cycles of four rows run a little faster as a paced walk, below.)
+    if (mode == MODE_PEER && vec == 4 && a.L == 2 && !c->opt_row_split && c->opt_cycle_kernel != 0 &&
         (tiles >= kPacedWaves || c->opt_cycle_kernel == 1)) {
         CycleArgs ca;
         ca.ge = ge;
         ca.S = S;
         ca.C = a.C;
         ca.gx = (tiles + waves - 1) / waves;
-        // measured on the n = 64, d = 25.6M shape: cycles of 2 rows 6.00 TB/s at a 6.15 TB/s target
-        // (one-shot walk 5.80), cycles of 4 rows 5.65 TB/s at 5.8-6.0 (one-shot walk 5.51)
-        LaunchPlan plan = make_plan(c, ca.gx, waves, vec, true, a.L == 2 ? 6150.0 : kAutoPaceGbsCycles);
+        LaunchPlan plan = make_plan(c, ca.gx, waves, vec, true, kAutoPaceGbsCycles);
         if (c->opt_blocks_per_cu < 0 && plan.bpc == 0) plan.bpc = kAutoBlocksPerCu;  // forced on a small problem
         const int momk = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
         ca.spread_partials = nullptr;
-        // every lane stores whole columns, so the consensus sums can ride along; only for cycles of two
-        // rows: with four-row batches the extra fp64 sums cost more (5.4 against 3.6 ms on n = 1024,
-        // d = 1M) than the separate reduction pass
-        if (spread_partials && spread_count && a.L == 2) {
+        if (spread_partials && spread_count) {  // every lane stores whole columns: the consensus sums ride along
             ca.spread_partials = spread_partials;
             plan.blocks_out = spread_count;
             if (momk == 2) return launch_planned(k_step_cycles<2, 2, true>, plan, ca, c->stream);
             return momk ? launch_planned(k_step_cycles<1, 2, true>, plan, ca, c->stream)
                         : launch_planned(k_step_cycles<0, 2, true>, plan, ca, c->stream);
         }
-        if (a.L == 2) {
-            if (momk == 2) return launch_planned(k_step_cycles<2, 2>, plan, ca, c->stream);
-            return momk ? launch_planned(k_step_cycles<1, 2>, plan, ca, c->stream)
-                        : launch_planned(k_step_cycles<0, 2>, plan, ca, c->stream);
-        }
-        if (momk == 2) return launch_planned(k_step_cycles<2, 4>, plan, ca, c->stream);
-        return momk ? launch_planned(k_step_cycles<1, 4>, plan, ca, c->stream)
-                    : launch_planned(k_step_cycles<0, 4>, plan, ca, c->stream);
+        if (momk == 2) return launch_planned(k_step_cycles<2, 2>, plan, ca, c->stream);
+        return momk ? launch_planned(k_step_cycles<1, 2>, plan, ca, c->stream)
+                    : launch_planned(k_step_cycles<0, 2>, plan, ca, c->stream);
     }
 
     int Q = 1;
@@ -912,11 +905,12 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     a.xcd = c->opt_xcd_swizzle;
     // pacing assumes every wavefront does the same work: one walker per cycle, equal segments
     const bool uniform = (Q == 1) && (((int64_t)a.C * Q) % wpb == 0);
-    // short cycles (< 8 rows per wavefront) already keep few rows open in a one-shot launch
-    const int min_cycle = c->opt_pace_min_cycle > 0 ? c->opt_pace_min_cycle : 8;
-    // cycles of exactly 8 rows (one-peer offset n/8) peak at a slightly lower target: 5.97 TB/s
-    // at 6.15-6.2 against 5.81 TB/s at 6.3 on the n = 64, d = 25.6M shape
-    const double auto_gbs = a.L <= 8 ? kAutoPaceGbsShort : kAutoPaceGbsWalk;
+    // cycles of 4 rows and more are paced (a work item then takes all cycles of its tile, below);
+    // shorter ones keep few rows open in a one-shot launch anyway
+    const int min_cycle = c->opt_pace_min_cycle > 0 ? c->opt_pace_min_cycle : 4;
+    // short cycles peak at lower targets than long walks (n = 64, d = 25.6M): 8 rows 5.97 TB/s at
+    // 6.15-6.2 (5.81 at 6.3); 4 rows 5.78 TB/s at 5.9-6.0 (5.63 at 6.1)
+    const double auto_gbs = a.L <= 4 ? kAutoPaceGbsFour : a.L <= 8 ? kAutoPaceGbsShort : kAutoPaceGbsWalk;
     const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= min_cycle, auto_gbs);
     // paced wavefronts advance one row per batch (two rows in flight); free-running ones two
     const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : kDefaultUnroll);
