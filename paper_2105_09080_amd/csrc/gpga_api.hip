@@ -219,7 +219,7 @@ gpga_status run_grad(gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out
         s = grow_f32(c, &c->coef, &c->coef_cap, (size_t)2 * c->n * Beff);
         if (s != GPGA_OK) return s;
         if (c->problem == PROB_LOGREG_VIRTUAL) {
-            size_t need = (size_t)c->n * Beff;
+            size_t need = (size_t)c->n * Beff * (size_t)virtual_margin_chunks(c);
             const size_t cons = consensus_partials_needed(c);
             if (need < cons) need = cons;
             s = grow_f64(c, &c->partials, &c->partials_cap, need);

@@ -252,8 +252,9 @@ __device__ __forceinline__ v4f virtual_quad(v4f mu, uint32_t c4, uint32_t i, uin
 
 // Pass 1: grid (column chunks, node).  Each lane owns column quads and keeps B
 // partial margins; the node shift mu_i is generated once per quad and reused for
-// all B samples.  Partial margins are combined per workgroup and added into
-// zpart[i][b] (fp64 atomics: order-independent to well below fp32 resolution).
+// all B samples.  Partial margins are combined per workgroup and stored as
+// zpart[i][b][chunk]; the coefficient kernel adds the chunks in a fixed order, so the
+// result does not depend on the order in which workgroups finish.
 template <int BMAX>
 __global__ void __launch_bounds__(256) k_virtual_margin(const float* __restrict__ x, int64_t ld,
                                                         int64_t d, const int32_t* __restrict__ idx,
@@ -290,17 +291,19 @@ __global__ void __launch_bounds__(256) k_virtual_margin(const float* __restrict_
     for (int b = 0; b < BMAX; ++b) {
         if (b < B) {
             const double t = block_sum(acc[b], s_buf);
-            if (threadIdx.x == 0) atomicAdd(&zpart[(int64_t)i * B + b], t);
+            if (threadIdx.x == 0) zpart[((int64_t)i * B + b) * gridDim.x + blockIdx.x] = t;
             __syncthreads();
         }
     }
 }
 
-__global__ void k_virtual_coef(const double* __restrict__ zpart, const float* __restrict__ y,
+__global__ void k_virtual_coef(const double* __restrict__ zpart, int32_t chunks, const float* __restrict__ y,
                                const int32_t* __restrict__ idx, int32_t B, int32_t M, int32_t n,
                                float* __restrict__ coef, float* __restrict__ lossterm) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (int64_t)n * B) return;
+    double z = 0.0;
+    for (int32_t ch = 0; ch < chunks; ++ch) z += zpart[t * chunks + ch];
     const int i = (int)(t / B);
     float cf, ls;
     const int32_t r = idx[t];
@@ -309,7 +312,7 @@ __global__ void k_virtual_coef(const double* __restrict__ zpart, const float* __
         lossterm[t] = __builtin_nanf("");
         return;
     }
-    sample_terms<PROB_LOGREG>(zpart[t], y[(int64_t)i * M + r], 1.0f / (float)B, &cf, &ls);
+    sample_terms<PROB_LOGREG>(z, y[(int64_t)i * M + r], 1.0f / (float)B, &cf, &ls);
     coef[t] = cf;
     lossterm[t] = ls;
 }
@@ -352,11 +355,6 @@ __global__ void __launch_bounds__(256) k_virtual_accum(const float* __restrict__
         if (c + 2 < d) row[c + 2] = (float)a2;
         if (c + 3 < d) row[c + 3] = (float)a3;
     }
-}
-
-__global__ void k_zero_f64(double* p, int64_t count) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < count) p[t] = 0.0;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -402,28 +400,34 @@ hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, fl
     return hipGetLastError();
 }
 
-hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out) {
-    constexpr int BMAX = 32;
-    if (B > BMAX) return hipErrorInvalidValue;
-    float* coef = c->coef;
-    float* lossterm = c->coef + (size_t)c->n * B;
-    double* zpart = c->partials;  // n*B doubles, sized by the caller
-    const uint32_t k0 = (uint32_t)(c->seed & 0xffffffffu), k1 = (uint32_t)(c->seed >> 32);
-    const int64_t nb = (int64_t)c->n * B;
-    hipLaunchKernelGGL(k_zero_f64, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, c->stream,
-                       zpart, nb);
+// Column chunks per node of the margin pass: enough workgroups per node to fill the chip, at least
+// 256 quads each, every chunk non-empty.
+int64_t virtual_margin_chunks(const gpga_ctx* c) {
     const int64_t d4 = (c->d + 3) / 4;
-    // enough workgroups per node to fill the chip, at least 256 quads each
     int64_t chunks = (4096 + c->n - 1) / c->n;
     const int64_t max_chunks = (d4 + 255) / 256;
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
     const int64_t qpb = (d4 + chunks - 1) / chunks;
-    dim3 grid1((unsigned)((d4 + qpb - 1) / qpb), (unsigned)c->n), block(256);
+    return (d4 + qpb - 1) / qpb;
+}
+
+hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out) {
+    constexpr int BMAX = 32;
+    if (B > BMAX) return hipErrorInvalidValue;
+    float* coef = c->coef;
+    float* lossterm = c->coef + (size_t)c->n * B;
+    double* zpart = c->partials;  // n*B*chunks doubles, sized by the caller (n * B * virtual_margin_chunks)
+    const uint32_t k0 = (uint32_t)(c->seed & 0xffffffffu), k1 = (uint32_t)(c->seed >> 32);
+    const int64_t nb = (int64_t)c->n * B;
+    const int64_t d4 = (c->d + 3) / 4;
+    const int64_t chunks = virtual_margin_chunks(c);
+    const int64_t qpb = (d4 + chunks - 1) / chunks;
+    dim3 grid1((unsigned)chunks, (unsigned)c->n), block(256);
     hipLaunchKernelGGL((k_virtual_margin<BMAX>), grid1, block, 0, c->stream, c->x, c->ld, c->d, idx,
                        B, k0, k1, c->mu_sigma, qpb, zpart);
     hipLaunchKernelGGL(k_virtual_coef, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, c->stream,
-                       zpart, c->tgt, idx, B, c->M, c->n, coef, lossterm);
+                       zpart, (int32_t)chunks, c->tgt, idx, B, c->M, c->n, coef, lossterm);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (loss_out) {

@@ -162,6 +162,8 @@ double mixing_beta(int32_t n, const HostCsr& w);
 hipError_t launch_synth_grad(const gpga_ctx* c);
 hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
 hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
+// Column chunks per node of the virtual-feature margin pass; it needs n * B * chunks doubles in c->partials.
+int64_t virtual_margin_chunks(const gpga_ctx* c);
 
 // Reductions and fills.
 hipError_t launch_fill_rows(const gpga_ctx* c, float* dst, const float* row_or_null);

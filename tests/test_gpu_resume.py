@@ -118,3 +118,24 @@ def test_run_with_adaptive_averaging_equals_explicit_aga_steps(hx):
     assert len(set(periods)) >= 2                      # the period did adapt along the way
     assert torch.equal(a.X, b_.X) and torch.equal(a.M, b_.M)
     a.close(), b_.close()
+
+
+def test_virtual_feature_gradient_is_reproducible_bit_for_bit(hx):
+    # margins are combined from per-chunk partials in a fixed order (no floating-point atomics)
+    n, d, M, Bsz = 8, 200_000, 50, 16
+    y = inputs.virtual_labels(n, M, seed=3)
+    idx = inputs.batch_indices(1, n, Bsz, M, seed=3)
+    X = inputs.random_state(n, d, seed=3)[0]
+    outs = []
+    for _ in range(3):
+        sim = hx.Simulation(n, d, topology="ring", H=0, lr=0.1, momentum=0.0)
+        sim.problem_logreg_virtual(3, y, 0.5)
+        idx_d = sim.upload_batches(idx)
+        sim.set_state(X=X)
+        sim.local_grad(idx_d[0])
+        loss = sim.local_loss(idx_d[0])
+        torch.cuda.synchronize()
+        outs.append((sim.G.clone(), loss.clone()))
+        sim.close()
+    for G, loss in outs[1:]:
+        assert torch.equal(G, outs[0][0]) and torch.equal(loss, outs[0][1])
