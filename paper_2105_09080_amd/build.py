@@ -15,7 +15,6 @@ SOURCES = ["gpga_api.hip", "gpga_step.hip", "gpga_mix.hip", "gpga_graph.hip", "g
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     "-fno-gpu-rdc",
-    "-munsafe-fp-atomics",
     # packed-FP32 instructions are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
