@@ -32,8 +32,8 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 # (FETCH_SIZE run + WRITE_SIZE run, scaled by a copy kernel of known size); the
 # summaries live under profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3/ring": 32768386656,    # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
-    "cfg4/expo1": 140805605779,  # profiles/step_cfg4_expo1.md (k_step_walk; k_step_cycles 140803967520)
+    "cfg3/ring": 32768370216,    # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
+    "cfg4/expo1": 140803063107,  # profiles/step_cfg4_expo1.md (k_step_walk, all five offsets)
     "cfg3/grid": 32768096911,    # profiles/step_tile_cfg3_grid.md (k_step_tile)
 }
 
