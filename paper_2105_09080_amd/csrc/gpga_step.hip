@@ -22,11 +22,20 @@
 // the last two y values kept in registers.  When a cycle is split over Q
 // wavefronts of a workgroup (few columns, many rows) the first/last y of every
 // segment are staged through LDS, so neighbour rows are never re-read from HBM.
+// Large problems run as persistent launches paced against the chip's clock (see
+// gpga_pace.hpp): every wavefront is then at the same row at the same time, a
+// paced one-peer work item takes all cycles of its column tile in turn, and
+// one-peer cycles of two rows have a kernel of their own whose batches are whole
+// cycles (k_step_cycles).  A tracing variant also sums the squared deviations of
+// what it stores from the column means (the consensus distance of the new X).
 //
-// Global-average kernel.  Rows are spread over (row lanes of a wave) x (waves
-// of the workgroup); partial column sums are combined with a wavefront
-// shuffle (xor butterfly) and then an LDS tree across waves.  Every row gets
-// the same bits of the mean, so the rows are bit-identical afterwards.
+// Global-average kernel.  Small problems: rows are spread over (row lanes of a
+// wave) x (waves of the workgroup); partial column sums are combined with a
+// wavefront shuffle (xor butterfly) and then an LDS tree across waves.  Large
+// problems: one lane sums its whole column while walking it, and the n copies
+// of the mean are stored row by row while the wavefront already reads its next
+// tile.  Every row gets the same bits of the mean, so the rows are bit-identical
+// afterwards.
 #include <type_traits>
 
 #include "gpga_internal.hpp"
