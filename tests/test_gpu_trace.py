@@ -34,6 +34,7 @@ CASES = [
     (64, 300_004, "expo1", 0, 0.9, 7, {}),                    # several cycles: reduction pass
     (64, 600_000, "expo1", 0, 0.9, 7, {"blocks_per_cu": 2, "pace_gbs": 4000}),   # paced: one walker takes all cycles
     (64, 600_000, "expo1", 6, 0.9, 8, {"blocks_per_cu": 4, "pace_gbs": 9000, "unroll": 2}),
+    (24, 600_000, "expo1", 0, 0.9, 6, {"blocks_per_cu": 2, "pace_gbs": 4000}),   # n not a power of two
     (16, 1003, "ring", 5, 0.9, 6, {}),                        # ragged d: scalar tail -> reduction pass
     (20, 2000, "grid", 4, 0.9, 6, {}),                        # sparse W
     (12, 500, "none", 3, 0.5, 5, {}),
@@ -50,8 +51,13 @@ def test_trace_matches_the_oracles_consensus_distance(hx, n, d, topology, H, mom
     want, norms = [], []
     for k in range(T):
         sim.local_grad()
+        X_prev, M_prev, G_prev = host(sim.X), (host(sim.M) if momentum else None), host(sim.G)
         sim.step()
         X = host(sim.X)
+        # the traced launches are also ordinary steps: one oracle step from the GPU's previous state
+        X1, _ = orc.gossip_pga_step(X_prev, M_prev if momentum else np.zeros_like(X_prev), G_prev, k,
+                                    topology=topology, H=H, lr=float(np.float32(0.05)), momentum=momentum)
+        assert np.abs(X - X1).max() <= 1e-5 * np.abs(X1).max(), k
         want.append(orc.consensus_error(X))               # definition applied to the GPU's own iterate
         norms.append(np.linalg.norm(X))
         if orc.is_global_step(k, H):
