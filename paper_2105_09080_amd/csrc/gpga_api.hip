@@ -237,7 +237,7 @@ gpga_status run_grad(gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out
 
 extern "C" {
 
-const char* gpga_version(void) { return "libgpga 0.1 (gfx950)"; }
+const char* gpga_version(void) { return "libgpga 0.2 (gfx950)"; }
 
 gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, int64_t H, float lr,
                         float momentum) {
