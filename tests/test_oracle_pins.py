@@ -390,6 +390,27 @@ def test_counter_normals_have_standard_moments_and_independent_lanes():
     assert abs((np.abs(flat) > 3).mean() - 0.0026998) < 5 * math.sqrt(0.0027 / N)
 
 
+def test_box_muller_pairs_invert_to_their_own_uniform_words():
+    # Box-Muller read backwards: the squared radius of a pair is -2 ln u_a and its angle
+    # 2 pi u_b, with (u_a, u_b) from words (r0, r1) for columns 0, 1 and (r2, r3) for columns
+    # 2, 3 of a quad.  The words come from the generator pinned by the known-answer vectors.
+    seed, node, j = 0x1234567890, 5, 9
+    c4 = np.arange(4096)
+    z = orc.counter_normals(seed, orc.TAG_FEAT, node, j, c4)
+    r = orc.philox4x32_10(c4, node, j, orc.TAG_FEAT, seed & 0xFFFFFFFF, seed >> 32)
+    u = [((np.asarray(w, dtype=np.uint64) >> np.uint64(9)).astype(np.float64) + 0.5) / 2.0 ** 23 for w in r]
+    for pair, (ua, ub) in enumerate(((u[0], u[1]), (u[2], u[3]))):
+        a, b = z[:, 2 * pair], z[:, 2 * pair + 1]
+        np.testing.assert_allclose(np.exp(-0.5 * (a * a + b * b)), ua, rtol=1e-12)
+        turn = np.mod(np.arctan2(b, a) / (2.0 * np.pi), 1.0)
+        gap = np.abs(turn - ub)
+        assert np.minimum(gap, 1.0 - gap).max() < 1e-12
+    # the two pairs of a quad are independent draws: their squared radii are uncorrelated
+    z = orc.counter_normals(7, orc.TAG_GRAD, 3, 11, np.arange(100_000))
+    ra2, rb2 = z[:, 0] ** 2 + z[:, 1] ** 2, z[:, 2] ** 2 + z[:, 3] ** 2
+    assert abs(np.corrcoef(ra2, rb2)[0, 1]) < 5 / math.sqrt(len(ra2))
+
+
 def test_synthetic_gradient_addressing_and_variance():
     n, var = 4, 1e-3
     full = orc.synthetic_grad(0, 5, n, np.arange(64), var)
@@ -412,6 +433,14 @@ def test_virtual_feature_gradient_equals_gradient_on_materialised_features():
     G1 = orc.logreg_virtual_grad(seed, y, X, idx, mu_var, chunk=16)
     G2 = orc.logreg_grad(feat, y, X, idx)
     np.testing.assert_allclose(G1, G2, atol=1e-13)
+    # the node shift is a draw of its own: uncorrelated with the noise of any sample
+    cols = np.arange(20_000)
+    mu = orc.virtual_features(seed, 1, np.arange(3000), cols[:50], mu_var).mean(axis=0)   # ~ mu_1[:50]
+    shift = orc.virtual_features(seed, 1, [0], cols, 1.0)[0] - orc.virtual_features(seed, 1, [0], cols, 0.0)[0]
+    np.testing.assert_allclose(shift[:50] * math.sqrt(mu_var), mu, atol=5 / math.sqrt(3000))
+    for m in range(4):
+        zeta = orc.virtual_features(seed, 1, [m], cols, 0.0)[0]
+        assert abs(np.corrcoef(shift, zeta)[0, 1]) < 5 / math.sqrt(len(cols))
     # node shift: sample mean over many samples approaches mu_i, with variance mu_var across columns
     cols = np.arange(2000)
     h = orc.virtual_features(seed, 1, np.arange(400), cols, mu_var)
@@ -468,13 +497,26 @@ def test_aga_period_schedule_on_a_hand_worked_example():
     assert sim.F_init == 2.0
 
 
+def test_aga_warm_up_ends_with_iteration_K_w_itself():
+    # Algorithm 2 tests k < K_w: an average that falls on k = K_w already adapts the period
+    n, d = 3, 2
+    sim = orc.GossipAGA(n, d, topology="ring", H_init=2, warmup_iters=3, H_max=10, lr=0.1, storage="f64")
+    Z = np.zeros((n, d))
+    for k in range(4):
+        sim.step(Z, np.full(n, 4.0))
+    # k=1: warm-up, F_init = (0 + 4)/2 = 2;  k=3 = K_w: H = ceil(2 / 4 * 2) = 1, F_init untouched
+    assert sim.history == [(1, 2), (3, 1)] and sim.F_init == 2.0
+
+
 def test_aga_with_constant_period_is_gossip_pga():
     # losses chosen so that ceil(F_init / F * H_init) stays H_init: the counter schedule
     # then averages exactly when mod(k+1, H) = 0, i.e. Algorithm 1
     n, d, H = 6, 4, 3
-    aga = orc.GossipAGA(n, d, topology="expo1", H_init=H, warmup_iters=7, H_max=50, lr=0.05, momentum=0.9,
+    def lr(k):                                            # a schedule: both must read gamma_k at the same k
+        return 0.05 * 0.9 ** k
+    aga = orc.GossipAGA(n, d, topology="expo1", H_init=H, warmup_iters=7, H_max=50, lr=lr, momentum=0.9,
                         storage="f64")
-    pga = orc.GossipPGA(n, d, topology="expo1", H=H, lr=0.05, momentum=0.9, storage="f64")
+    pga = orc.GossipPGA(n, d, topology="expo1", H=H, lr=lr, momentum=0.9, storage="f64")
     for k in range(20):
         G = RNG.standard_normal((n, d))
         # warm-up (k = 2, 5 < 7) sees F = 4, 4: F_init = 2, then 3; afterwards F = 3.2 gives
