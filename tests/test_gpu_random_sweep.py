@@ -1,0 +1,142 @@
+"""Seeded random sweep of valid step configurations (shape, padding, topology, momentum,
+averaging period, iteration counter, launch options, consensus trace) against the CPU
+oracle, through the C ABI.  Every case checks two consecutive steps: iterates, momentum,
+what happens to g, untouched padding columns, consensus distance (call and trace), node
+mean, and identical rows after a global average."""
+import json
+
+import numpy as np
+import pytest
+
+from oracle import gpga_oracle as orc
+from paper_2105_09080_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+SENTINEL = 12345.0
+LR = float(np.float32(0.3))
+
+N_CHOICES = [1, 2, 3, 4, 5, 7, 8, 12, 16, 20, 31, 32, 33, 48, 63, 64, 65, 100, 128, 129, 200, 256, 257, 300, 1024]
+D_CHOICES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1000, 1023, 1024, 1025, 4096, 4100, 10_000, 65_536, 65_540,
+             100_001, 300_004, 1_000_000]
+OPTION_CHOICES = (("unroll", [1, 2, 4, 8]), ("waves", [1, 2, 4, 8]), ("row_split", [1, 2, 4, 8]), ("row_lanes", [1, 2, 4]),
+                  ("xcd_swizzle", [0, 1]), ("blocks_per_cu", [0, 1, 2, 4, 8]), ("pace_gbs", [0, 2000, 6000, 16000]),
+                  ("cycle_kernel", [0, 1]), ("pace_min_cycle", [2, 4, 8, 64]), ("mix_two_pass", [0, 1]),
+                  ("mix_waves", [2, 4, 8, 16]), ("mix_lane_bytes", [4, 8, 16]))
+
+
+@pytest.fixture(scope="module")
+def hx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2105_09080_amd import harness
+    return harness
+
+
+def draw_case(rng):
+    def pick(xs):
+        return xs[int(rng.integers(len(xs)))]
+    n = int(pick(N_CHOICES))
+    d = max(1, min(int(pick(D_CHOICES)), 3_000_000 // n))          # keeps the dense oracle quick
+    mu = float(pick([0.0, 0.5, 0.9]))
+    case = dict(n=n, d=d, pad=int(pick([0, 0, 0, 1, 2, 3, 4, 8, 13])),
+                topology=pick(["ring", "expo1", "none", "full", "grid", "expo", "custom"]), momentum=mu,
+                nesterov=bool(mu > 0 and rng.random() < 0.3), H=int(pick([0, 0, 1, 2, 3, 5])),
+                k=int(pick([0, 1, 2, 3, 4, 5, 6, 7, 11, 12345])), options={}, trace=bool(rng.random() < 0.5),
+                terms=int(pick([1, 3, 6])))
+    if rng.random() < 0.7:
+        for name, values in OPTION_CHOICES:
+            if rng.random() < 0.35:
+                case["options"][name] = int(pick(values))
+    return case
+
+
+def random_doubly_stochastic(n, terms, rng):
+    w = rng.random(terms + 1)
+    w /= w.sum()
+    W = w[0] * np.eye(n)
+    for t in range(terms):
+        W += w[t + 1] * np.eye(n)[rng.permutation(n)]
+    return W.astype(np.float32).astype(np.float64)
+
+
+def check_case(hx, case, seed, rng):
+    from paper_2105_09080_amd import binding as B
+    n, d, topology, mu, H, k = case["n"], case["d"], case["topology"], case["momentum"], case["H"], case["k"]
+    nesterov = case["nesterov"]
+    X, Mb, G = inputs.random_state(n, d, seed=seed)
+    W = random_doubly_stochastic(n, case["terms"], rng) if topology == "custom" else None
+    sim = hx.Simulation(n, d, topology=topology, H=H, lr=0.3, momentum=mu, ld=d + case["pad"])
+    buffers = sim._bufs + [sim.g] + ([sim.m] if sim.m is not None else [])
+    for t in buffers:
+        t.fill_(SENTINEL)
+    torch.cuda.synchronize()
+    if W is not None:
+        sim.set_mixing(W)
+    if nesterov:
+        sim.set_nesterov(True)
+    applied = {}
+    for name, v in case["options"].items():
+        try:
+            sim.set_option(name, v)
+            applied[name] = v
+        except B.GpgaError:                       # a combination the library refuses (row_split > waves)
+            pass
+    trace = sim.attach_trace(k + 4) if case["trace"] else None
+    sim.set_state(X=X, M=Mb, G=G, k=k)
+    X_ref = X.astype(np.float64)
+    M_ref = (Mb if mu else np.zeros_like(Mb)).astype(np.float64)
+    G_now = G.astype(np.float64)
+    problems = []
+    for j in range(2):
+        is_global = orc.is_global_step(k + j, H)
+        sparse = topology in ("grid", "expo", "custom") and n > 1 and not is_global
+        two_pass = sparse and (n > 256 or applied.get("mix_two_pass") == 1)
+        sim.step()
+        Y_ref, _ = orc.local_update(X_ref, M_ref, G_now, LR, mu, nesterov)
+        X_next, M_next = orc.gossip_pga_step(X_ref, M_ref, G_now, k + j, topology=topology, H=H, lr=LR, momentum=mu,
+                                             nesterov=nesterov, W=W)
+        X_ref = X_next.astype(np.float32).astype(np.float64)
+        M_ref = M_next.astype(np.float32).astype(np.float64)
+        # a few ulp of the step's input scale (a global average at d = 1 can cancel to nearly 0)
+        scale = max(np.abs(X_ref).max(), np.abs(Y_ref).max(), 1e-30)
+        X_gpu = sim.X.cpu().numpy().astype(np.float64)
+        err = {"X": np.abs(X_gpu - X_ref).max() / scale}
+        if mu:
+            err["M"] = np.abs(sim.M.cpu().numpy() - M_ref).max() / max(np.abs(M_ref).max(), 1e-30)
+        G_gpu = sim.G.cpu().numpy().astype(np.float64)
+        if two_pass:                              # documented side effect: g then holds x^(k+1/2)
+            err["g = y"] = np.abs(G_gpu - Y_ref).max() / scale
+            G_now = G_gpu
+        elif not np.array_equal(G_gpu, G_now):
+            problems.append(f"step {j}: g was modified")
+        if not all(bool((t[:, d:] == SENTINEL).all().item()) for t in buffers):
+            problems.append(f"step {j}: padding columns were written")
+        norm = np.linalg.norm(X_ref) + 1e-30
+        ce_ref = orc.consensus_error(X_ref)
+        err["consensus"] = abs(sim.consensus_error() - ce_ref) / norm
+        if trace is not None:
+            err["trace"] = abs(float(trace[k + j].item()) - ce_ref) / norm
+        err["mean"] = np.abs(sim.mean().cpu().numpy() - orc.node_mean(X_ref)).max() / scale
+        if is_global or topology == "full":
+            rows = sim.X.cpu().numpy()
+            if not all(np.array_equal(rows[0], rows[i]) for i in range(n)):
+                problems.append(f"step {j}: rows differ after a global average")
+        problems += [f"step {j}: {what} off by {e:.3e}" for what, e in err.items() if not e <= TOL]
+    sim.close()
+    return problems
+
+
+@pytest.mark.parametrize("seed", [101, 202, 303, 404])
+def test_random_valid_configurations_match_the_oracle(hx, seed):
+    rng = np.random.default_rng(seed)
+    failures = []
+    for j in range(150):
+        case = draw_case(rng)
+        print("case", seed, j, json.dumps(case), flush=True)       # names the case should a launch go wrong
+        problems = check_case(hx, case, seed * 1000 + j, rng)
+        if problems:
+            failures.append((j, case, problems))
+    assert not failures, failures[:5]
