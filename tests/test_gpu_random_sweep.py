@@ -1,8 +1,15 @@
-"""Seeded random sweep of valid step configurations (shape, padding, topology, momentum,
+"""Seeded random sweeps against the CPU oracle, through the C ABI.
+
+Steps: valid step configurations (shape, padding, topology, momentum,
 averaging period, iteration counter, launch options, consensus trace) against the CPU
 oracle, through the C ABI.  Every case checks two consecutive steps: iterates, momentum,
 what happens to g, untouched padding columns, consensus distance (call and trace), node
-mean, and identical rows after a global average."""
+mean, and identical rows after a global average.
+
+Gradients: the four problems (least squares, logistic, logistic with regenerated
+features, counter-addressed synthetic) over random n, d, M, minibatch sizes (0 = full
+batch), padding and iteration counters: gradient, minibatch loss, untouched x and padding."""
+import math
 import json
 
 import numpy as np
@@ -137,6 +144,89 @@ def test_random_valid_configurations_match_the_oracle(hx, seed):
         case = draw_case(rng)
         print("case", seed, j, json.dumps(case), flush=True)       # names the case should a launch go wrong
         problems = check_case(hx, case, seed * 1000 + j, rng)
+        if problems:
+            failures.append((j, case, problems))
+    assert not failures, failures[:5]
+
+
+def check_gradient_case(hx, case, seed):
+    prob, n, d, M, Bsz, k = case["problem"], case["n"], case["d"], case["M"], case["B"], case["k"]
+    sim = hx.Simulation(n, d, topology="ring", H=0, lr=0.1, momentum=0.0, ld=d + case["pad"])
+    buffers = sim._bufs + [sim.g]
+    for t in buffers:
+        t.fill_(SENTINEL)
+    torch.cuda.synchronize()
+    X = inputs.random_state(n, d, seed=seed, scale=case["x_scale"])[0]
+    sim.set_state(X=X, k=k)
+    idx = inputs.batch_indices(1, n, Bsz, M, seed=seed + 1)[0] if Bsz else None
+    loss = loss_ref = None
+    if prob == "synthetic":
+        sim.problem_synthetic(seed, 1e-3)
+        sim.local_grad()
+        G_ref = orc.synthetic_grad(seed, k, n, np.arange(d), 1e-3)
+    elif prob == "virtual":
+        y = inputs.virtual_labels(n, M, seed)
+        sim.problem_logreg_virtual(seed, y, 0.5)
+        sim.local_grad(sim.upload_batches(idx))
+        G_ref = orc.logreg_virtual_grad(seed, y, X, idx, 0.5)
+    else:
+        make, attach, grad, loss_of = {
+            "lsq": (inputs.lsq_problem, sim.problem_lsq, orc.lsq_grad, orc.lsq_loss),
+            "logreg": (inputs.logreg_problem, sim.problem_logreg, orc.logreg_grad, orc.logreg_loss)}[prob]
+        data, target, _ = make(n, d, M, seed=seed)
+        attach(data, target)
+        idx_d = sim.upload_batches(idx) if Bsz else None
+        sim.local_grad(idx_d)
+        loss = sim.local_loss(idx_d).cpu().numpy().astype(np.float64)
+        G_ref, loss_ref = grad(data, target, X, idx), loss_of(data, target, X, idx)
+    problems = []
+    e = np.abs(sim.G.cpu().numpy() - G_ref).max() / max(np.abs(G_ref).max(), 1e-30)
+    if not e <= TOL:
+        problems.append(f"gradient off by {e:.3e}")
+    if loss_ref is not None:
+        e = np.abs(loss - loss_ref).max() / max(np.abs(loss_ref).max(), 1e-30)
+        if not e <= TOL:
+            problems.append(f"loss off by {e:.3e}")
+    if not all(bool((t[:, d:] == SENTINEL).all().item()) for t in buffers):
+        problems.append("padding columns were written")
+    if not np.array_equal(sim.X.cpu().numpy(), X):
+        problems.append("x was modified")
+    sim.close()
+    return problems
+
+
+def draw_gradient_case(rng):
+    def pick(xs):
+        return xs[int(rng.integers(len(xs)))]
+    prob = pick(["lsq", "logreg", "virtual", "synthetic"])
+    n = int(pick([1, 2, 3, 5, 8, 17, 32, 64]))
+    d = int(pick([1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1000, 1023, 1025, 4096, 4099, 10_000, 20_000, 65_540]))
+    M = int(pick([1, 2, 7, 20, 33, 64, 100]))
+    Bsz = int(pick([0, 1, 2, 6, 16, 32, 33, 50]))
+    x_scale = 1.0
+    if prob == "virtual":                          # needs an explicit minibatch of at most 32 samples
+        Bsz, d = min(max(Bsz, 1), 32), min(d, 20_000)
+        x_scale = 1.0 / math.sqrt(d)
+    elif prob == "logreg":
+        x_scale = float(pick([1.0, 0.3, 0.01, 30.0]))
+    if prob in ("lsq", "logreg"):
+        while n * M * d > 4_000_000:               # keeps the feature array small
+            if M > 7:
+                M = max(1, M // 2)
+            else:
+                d = max(1, d // 2)
+    return dict(problem=prob, n=n, d=d, M=M, B=Bsz, pad=int(pick([0, 0, 1, 3, 4])), k=int(pick([0, 1, 7, 123456])),
+                x_scale=x_scale)
+
+
+@pytest.mark.parametrize("seed", [11, 22])
+def test_random_gradient_configurations_match_the_oracle(hx, seed):
+    rng = np.random.default_rng(seed)
+    failures = []
+    for j in range(250):
+        case = draw_gradient_case(rng)
+        print("gradient case", seed, j, json.dumps(case), flush=True)
+        problems = check_gradient_case(hx, case, seed * 1000 + j)
         if problems:
             failures.append((j, case, problems))
     assert not failures, failures[:5]
