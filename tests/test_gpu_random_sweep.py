@@ -8,7 +8,13 @@ mean, and identical rows after a global average.
 
 Gradients: the four problems (least squares, logistic, logistic with regenerated
 features, counter-addressed synthetic) over random n, d, M, minibatch sizes (0 = full
-batch), padding and iteration counters: gradient, minibatch loss, untouched x and padding."""
+batch), padding and iteration counters: gradient, minibatch loss, untouched x and padding.
+
+Runs: T iterations of the whole loop on synthetic gradients (a linear map of the draws, so
+free-running trajectories stay comparable) over random topologies, periods, momentum forms,
+step-size schedules and starting counters, driven by one gpga_run, two, or explicit
+gradient + step calls: final iterate, momentum, iteration counter and the per-step
+consensus trace."""
 import math
 import json
 
@@ -227,6 +233,78 @@ def test_random_gradient_configurations_match_the_oracle(hx, seed):
         case = draw_gradient_case(rng)
         print("gradient case", seed, j, json.dumps(case), flush=True)
         problems = check_gradient_case(hx, case, seed * 1000 + j)
+        if problems:
+            failures.append((j, case, problems))
+    assert not failures, failures[:5]
+
+
+def check_run_case(hx, case, seed):
+    from paper_2105_09080_amd import binding as B
+    n, d, T, k0, mu = case["n"], case["d"], case["T"], case["k0"], case["momentum"]
+    base, var = 0.2, 1e-1
+    f32 = lambda v: float(np.float32(v))
+    x0 = inputs.initial_point(d, seed=seed)
+    sim = hx.Simulation(n, d, topology=case["topology"], H=case["H"], lr=base, momentum=mu, x0=x0)
+    if case["nesterov"]:
+        sim.set_nesterov(True)
+    if case["schedule"] == "step":
+        B.gpga_lr_schedule_step(sim.ctx, base, 4, 0.5)
+        lr = lambda k: orc.lr_step_decay(k, f32(base), 4, 0.5)
+    elif case["schedule"] == "milestones":
+        B.gpga_lr_schedule_milestones(sim.ctx, base, 3, 0.05, [6, 11], 0.1)
+        lr = lambda k: orc.lr_warmup_milestones(k, f32(base), 3, f32(0.05), [6, 11], f32(0.1))
+    elif case["schedule"] == "poly":
+        B.gpga_lr_schedule_poly(sim.ctx, base, 2, 30, 2.0)
+        lr = lambda k: orc.lr_poly(k, f32(base), 2, 30, 2.0)
+    else:
+        lr = base
+    sim.problem_synthetic(seed, var)
+    ref = orc.GossipPGA(n, d, topology=case["topology"], H=case["H"], lr=lr, momentum=mu, nesterov=case["nesterov"],
+                        x0=x0.astype(np.float32), storage="f32")
+    ref.k = k0
+    B.gpga_set_iter(sim.ctx, k0)
+    trace = sim.attach_trace(k0 + T)
+    if case["driver"] == "run":
+        sim.run(T)
+    elif case["driver"] == "two runs":
+        sim.run(T // 2)
+        sim.run(T - T // 2)
+    else:
+        for _ in range(T):
+            sim.local_grad()
+            sim.step()
+    consensus = []
+    for j in range(T):
+        ref.step(orc.synthetic_grad(seed, k0 + j, n, np.arange(d), var))
+        consensus.append(orc.consensus_error(ref.X))
+    err = {"X": np.abs(sim.X.cpu().numpy() - ref.X).max() / max(np.abs(ref.X).max(), 1e-30)}
+    if mu:
+        err["M"] = np.abs(sim.M.cpu().numpy() - ref.M).max() / max(np.abs(ref.M).max(), 1e-30)
+    err["trace"] = np.abs(trace.cpu().numpy()[k0:k0 + T] - np.array(consensus)).max() / (np.linalg.norm(ref.X) + 1e-30)
+    problems = [f"{what} off by {e:.3e}" for what, e in err.items() if not e <= 1e-4]
+    if sim.k != k0 + T:
+        problems.append(f"iteration counter {sim.k}, expected {k0 + T}")
+    sim.close()
+    return problems
+
+
+@pytest.mark.parametrize("seed", [7, 8])
+def test_random_runs_match_the_oracle_driver(hx, seed):
+    rng = np.random.default_rng(seed)
+
+    def pick(xs):
+        return xs[int(rng.integers(len(xs)))]
+    failures = []
+    for j in range(200):
+        n = int(pick([1, 2, 3, 5, 8, 12, 16, 20, 33, 64, 100, 257]))
+        mu = float(pick([0.0, 0.5, 0.9]))
+        case = dict(n=n, d=max(1, min(int(pick([1, 3, 4, 64, 257, 1000, 1024, 4100, 20_000])), 400_000 // n)),
+                    topology=pick(["ring", "expo1", "none", "full", "grid", "expo"]), momentum=mu,
+                    nesterov=bool(mu > 0 and rng.random() < 0.4), H=int(pick([0, 1, 2, 3, 4, 7])),
+                    T=int(pick([1, 2, 5, 9, 16, 25])), k0=int(pick([0, 0, 3, 10])),
+                    schedule=pick(["constant", "step", "milestones", "poly"]), driver=pick(["run", "two runs", "calls"]))
+        print("run case", seed, j, json.dumps(case), flush=True)
+        problems = check_run_case(hx, case, seed * 1000 + j)
         if problems:
             failures.append((j, case, problems))
     assert not failures, failures[:5]
