@@ -256,7 +256,8 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * "mix_two_pass" (1 = sparse-W gossip steps always take the two-pass path),
  * "mix_waves" (sparse-W tile kernel: wavefronts per workgroup, 0 = automatic, 2, 4,
  * 8, 16), "mix_lane_bytes" (sparse-W tile kernel: widest lane type allowed,
- * 0 = automatic, 4, 8, 16), "cycle_kernel" (whole-cycle kernel for one-peer offset
+ * 0 = automatic, 4, 8, 16), "mix_csr_lds" (sparse-W tile kernel: 1 = copy a small W
+ * into LDS (default), 0 = read it from global memory), "cycle_kernel" (whole-cycle kernel for one-peer offset
  * n/2: -1 = automatic (large problems), 0 = never, 1 = always),
  * "pace_min_cycle" (shortest row cycle whose walk is paced, 0 = automatic (4)),
  * "blocks_per_cu" (persistent launch of the fused step: -1 = automatic, 0 = one

@@ -264,6 +264,9 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
         c->num_cus = cus;
+    int lds = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, c->device) == hipSuccess && lds > 0)
+        c->max_lds_block = lds;
     int khz = 0;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && khz > 0)
         c->clock_hz = 1e3 * (double)khz;
@@ -785,6 +788,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "mix_two_pass")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_two_pass must be 0 or 1");
         c->opt_mix_two_pass = (int)value;
+    } else if (!strcmp(name, "mix_csr_lds")) {
+        if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_csr_lds must be 0 or 1");
+        c->opt_mix_csr_lds = (int)value;
     } else if (!strcmp(name, "pace_gbs")) {
         if (value < -1 || value > 16000) return fail(c, GPGA_EINVAL, "pace_gbs must be -1 (automatic), 0 (off) or a rate up to 16000 GB/s");
         c->opt_pace_gbs = (int)value;

@@ -80,8 +80,10 @@ struct gpga_ctx {
     int opt_mix_lane_bytes = 0;  // sparse-W tile kernel: widest lane type allowed (0 = automatic, 4, 8, 16)
     int opt_mix_waves = 0;       // sparse-W tile kernel: wavefronts per workgroup (0 = automatic, 2, 4, 8, 16)
     int opt_mix_two_pass = 0;  // 1 = sparse-W steps always take the two-pass path
+    int opt_mix_csr_lds = 1;   // 0 = the tile kernel reads W from global memory even when it fits in LDS
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
+    int max_lds_block = 64 * 1024;  // LDS bytes one workgroup may ask for on this device
     int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
     int opt_cycle_kernel = -1;   // whole-cycle kernel for one-peer cycles of 2 / 4 rows: -1 automatic, 0 never, 1 always
     int opt_pace_min_cycle = 0;  // shortest row cycle that is paced (0 = automatic)

@@ -50,6 +50,7 @@ struct TileArgs {
     StepGeom ge;
     CsrDev w;
     int64_t tiles;  // column tiles; workgroups stride over them
+    int32_t nnz;    // entries of W (the LDS copy needs the count)
     PaceArgs pace;
 };
 
@@ -57,8 +58,14 @@ constexpr int kTileWavesDefault = 4;
 constexpr int kTileWavesMax = 16;
 constexpr int kTileUnroll = 4;
 constexpr size_t kTileLdsBytes = 64 * 1024;
+constexpr size_t kTileCsrLdsBytes = 16 * 1024;  // largest W copied into LDS (two workgroups per CU still fit)
 
-template <typename T, int MOM>
+// LCSR: W is copied into LDS behind the tile once per workgroup and phase 2 reads it from
+// there.  Vector memory operations of a wavefront retire in order, so a neighbour list
+// fetched from global memory inside the output loop would make every output row wait for
+// the stores of the rows before it; LDS reads are counted separately and leave the stores
+// streaming.
+template <typename T, int MOM, bool LCSR>
 __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     extern __shared__ __align__(16) unsigned char s_raw[];
@@ -68,6 +75,17 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kTileWaves = blockDim.x >> 6;
     const int n = a.ge.n;
+    // LDS copy of W: row pointers (n + 1, padded to an even count), columns, weights
+    int32_t* __restrict__ s_ptr = reinterpret_cast<int32_t*>(s_raw + (size_t)n * kWave * sizeof(T));
+    int32_t* __restrict__ s_col = s_ptr + ((n + 2) & ~1);
+    float* __restrict__ s_val = reinterpret_cast<float*>(s_col + a.nnz);
+    if (LCSR) {  // visible to phase 2 through the barrier that ends the first phase 1
+        for (int p = threadIdx.x; p <= n; p += blockDim.x) s_ptr[p] = a.w.ptr[p];
+        for (int p = threadIdx.x; p < a.nnz; p += blockDim.x) {
+            s_col[p] = a.w.col[p];
+            s_val[p] = a.w.val[p];
+        }
+    }
     const int64_t ldT = a.ge.ld / V;
     const float lr = a.ge.lr, mu = a.ge.mu;
     constexpr uint32_t kLoadUnits = MOM ? 4u : 2u;  // 4-byte streams per row in phase 1 (reads + the m store)
@@ -87,7 +105,36 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
         T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
 
         // Phase 1: rows wave, wave + W, ... : local update, y into LDS.
-        for (int base = wave; base < n; base += kTileWaves * kTileUnroll) {
+        // Whole row groups of a whole tile first, in a loop of their own without lane or row
+        // predicates: all the loads of a group are issued back to back before the first use,
+        // and nothing makes them wait for the stores of the group before.
+        int base = wave;
+        if ((tile + 1) * kWave <= a.ge.ncols) {  // every lane has a column
+            for (; base + (kTileUnroll - 1) * kTileWaves < n; base += kTileWaves * kTileUnroll) {
+                T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
+                pace_wait(a.pace, t0, units_done);
+                units_done += kTileUnroll * kLoadUnits;
+#pragma unroll
+                for (int u = 0; u < kTileUnroll; ++u) {
+                    const int64_t off = (int64_t)(base + u * kTileWaves) * ldT;
+                    xv[u] = ld_stream(xp + off);
+                    if (MOM) mv[u] = ld_stream(mp + off);
+                    gv[u] = ld_stream(gp + off);
+                }
+#pragma unroll
+                for (int u = 0; u < kTileUnroll; ++u) {
+                    const int row = base + u * kTileWaves;
+                    T mom = gv[u];
+                    if (MOM) {
+                        mom = mu * mv[u] + gv[u];
+                        st_stream(mp + (int64_t)row * ldT, mom);
+                    }
+                    sy[row * kWave + lane] = half_step<MOM>(xv[u], gv[u], mom, lr, mu);
+                }
+            }
+        }
+        // Ragged row groups and the last, partial tile: predicated per row and per lane.
+        for (; base < n; base += kTileWaves * kTileUnroll) {
             T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
             pace_wait(a.pace, t0, units_done);
             units_done += kTileUnroll * kLoadUnits;
@@ -129,10 +176,10 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
             cj = 0;
             wv = 0.f;
             if (i < n) {
-                const int p = a.w.ptr[i] + c0 + lane;
-                if (p < a.w.ptr[i + 1]) {
-                    cj = a.w.col[p];
-                    wv = a.w.val[p];
+                const int p = (LCSR ? s_ptr[i] : a.w.ptr[i]) + c0 + lane;
+                if (p < (LCSR ? s_ptr[i + 1] : a.w.ptr[i + 1])) {
+                    cj = LCSR ? s_col[p] : a.w.col[p];
+                    wv = LCSR ? s_val[p] : a.w.val[p];
                 }
             }
         };
@@ -140,7 +187,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
         float wv_next;
         fetch_list(wave, 0, cj_next, wv_next);
         for (int i = wave; i < n; i += kTileWaves) {
-            const int cnt = a.w.ptr[i + 1] - a.w.ptr[i];
+            const int cnt = LCSR ? __builtin_amdgcn_readfirstlane(s_ptr[i + 1] - s_ptr[i]) : a.w.ptr[i + 1] - a.w.ptr[i];
             int cj_l = cj_next;
             float wv_l = wv_next;
             fetch_list(i + kTileWaves, 0, cj_next, wv_next);
@@ -199,7 +246,7 @@ __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, 
 }
 
 
-template <typename T, int MOM>
+template <typename T, int MOM, bool LCSR>
 hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds) {
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
@@ -214,13 +261,13 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
     const int want = c->opt_blocks_per_cu < 0 ? (gbs > 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
     if (want > 0) {
         int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM>, threads, lds) != hipSuccess || occ < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM, LCSR>, threads, lds) != hipSuccess || occ < 1)
             occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
         if (resident < blocks) blocks = resident;
         pace_setup(const_cast<gpga_ctx*>(c), gbs, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
-    hipLaunchKernelGGL((k_step_tile<T, MOM>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
+    hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
     return hipGetLastError();
 }
 
@@ -231,12 +278,21 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
     a.w = w;
     a.tiles = (ge.ncols + kWave - 1) / kWave;
     if (a.tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const size_t lds = (size_t)ge.n * kWave * sizeof(T);
+    a.nnz = (int32_t)c->csr.col.size();
+    const size_t tile_lds = (size_t)ge.n * kWave * sizeof(T);
+    // W rides along in LDS when it is small and the device grants the workgroup the room
+    const size_t csr_lds = ((((size_t)ge.n + 2) & ~(size_t)1) + 2 * (size_t)a.nnz) * sizeof(int32_t);
+    const bool lcsr = c->opt_mix_csr_lds != 0 && csr_lds <= kTileCsrLdsBytes && tile_lds + csr_lds <= (size_t)c->max_lds_block;
+    const size_t lds = tile_lds + (lcsr ? csr_lds : 0);
     // measured on the n = 64, d = 25.6M shape: 8 or 16 wavefronts per workgroup stream
     // 5.2-6.0 TB/s, 4 wavefronts 4.8-5.1 TB/s (more rows are in flight while others mix)
     const int waves = c->opt_mix_waves ? c->opt_mix_waves : (ge.n >= 32 ? 8 : kTileWavesDefault);
-    if (mom == 2) return launch_tile_mom<T, 2>(c, a, waves, lds);
-    return mom == 1 ? launch_tile_mom<T, 1>(c, a, waves, lds) : launch_tile_mom<T, 0>(c, a, waves, lds);
+    if (lcsr) {
+        if (mom == 2) return launch_tile_mom<T, 2, true>(c, a, waves, lds);
+        return mom == 1 ? launch_tile_mom<T, 1, true>(c, a, waves, lds) : launch_tile_mom<T, 0, true>(c, a, waves, lds);
+    }
+    if (mom == 2) return launch_tile_mom<T, 2, false>(c, a, waves, lds);
+    return mom == 1 ? launch_tile_mom<T, 1, false>(c, a, waves, lds) : launch_tile_mom<T, 0, false>(c, a, waves, lds);
 }
 
 template <typename T>

@@ -122,7 +122,8 @@ def test_two_pass_path_gives_the_tile_kernels_answer_and_leaves_y_in_g(hx, n, d,
 
 @pytest.mark.parametrize("opts", [{"blocks_per_cu": 1}, {"blocks_per_cu": 1, "pace_gbs": 3000},
                                   {"blocks_per_cu": 2, "pace_gbs": 8000, "mix_waves": 4}, {"mix_waves": 16},
-                                  {"mix_lane_bytes": 8}, {"mix_lane_bytes": 4, "mix_waves": 2}],
+                                  {"mix_lane_bytes": 8}, {"mix_lane_bytes": 4, "mix_waves": 2}, {"mix_csr_lds": 0},
+                                  {"mix_csr_lds": 0, "mix_lane_bytes": 8, "mix_waves": 4}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
 @pytest.mark.parametrize("topology", ["grid", "expo"])
 def test_tile_kernel_launch_shapes_give_the_same_answer(hx, topology, opts):
