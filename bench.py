@@ -34,7 +34,7 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 MEASURED_TRAFFIC_BYTES = {
     "cfg3/ring": 32768370216,    # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
     "cfg4/expo1": 140803063107,  # profiles/step_cfg4_expo1.md (k_step_walk, all five offsets)
-    "cfg3/grid": 32768096911,    # profiles/step_tile_cfg3_grid.md (k_step_tile)
+    "cfg3/grid": 32768074151,    # profiles/step_tile_cfg3_grid.md (k_step_tile)
 }
 
 
