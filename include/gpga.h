@@ -183,7 +183,15 @@ gpga_status gpga_step(gpga_ctx* ctx);
  * returns its status; iterations before it stay enqueued.  With adaptive averaging
  * enabled (gpga_aga_enable) every iteration is a gpga_aga_step instead, the library
  * evaluating the minibatch losses itself in the iterations that end in a global
- * average (those synchronise, as gpga_aga_step does). */
+ * average (those synchronise, as gpga_aga_step does).
+ * Small problems with stored features (least squares or logistic; n*d <= 8192,
+ * n*B <= 4096, n*B*d <= 2^17; the simulation of Sec. 5.1 is one) take a second form
+ * of the same loop unless option "small_run" is 0: whole iterations - gradients,
+ * momentum and local update, gossip step or global average, consensus trace - run
+ * inside single-workgroup launches of up to 256 iterations with the state in LDS.
+ * The results are the same to rounding; x is then updated IN PLACE (x / x_new are
+ * not swapped: gpga_current_x tells), m as usual, and g holds the gradients of the
+ * last iteration. */
 gpga_status gpga_run(gpga_ctx* ctx, int64_t T, const int32_t* batch_table_dev, int32_t B);
 
 /* Attach an arbitrary weight matrix W (Sec. 3: W >= 0, W 1 = 1, 1^T W = 1^T,
@@ -256,7 +264,9 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * "mix_two_pass" (1 = sparse-W gossip steps always take the two-pass path),
  * "mix_waves" (sparse-W tile kernel: wavefronts per workgroup, 0 = automatic, 2, 4,
  * 8, 16), "mix_lane_bytes" (sparse-W tile kernel: widest lane type allowed,
- * 0 = automatic, 4, 8, 16), "mix_csr_lds" (sparse-W tile kernel: 1 = copy a small W
+ * 0 = automatic, 4, 8, 16), "small_run" (gpga_run on small problems: 1 = whole
+ * iterations in single-workgroup launches (default), 0 = one kernel per stage),
+ * "mix_csr_lds" (sparse-W tile kernel: 1 = copy a small W
  * into LDS (default), 0 = read it from global memory), "cycle_kernel" (whole-cycle kernel for one-peer offset
  * n/2: -1 = automatic (large problems), 0 = never, 1 = always),
  * "pace_min_cycle" (shortest row cycle whose walk is paced, 0 = automatic (4)),

@@ -664,6 +664,22 @@ gpga_status gpga_run(gpga_ctx* c, int64_t T, const int32_t* batch_table_dev, int
         }
         return GPGA_OK;
     }
+    if (small_run_fits(c, batch_table_dev, B)) {
+        // the whole loop inside single-workgroup launches of up to kSmallRunMaxIters iterations
+        int32_t Beff = 0;
+        gpga_status s = check_batch(c, batch_table_dev, B, &Beff);
+        if (s != GPGA_OK) return s;
+        float lr[kSmallRunMaxIters];
+        for (int64_t j = 0; j < T;) {
+            const int32_t chunk = (int32_t)(T - j < kSmallRunMaxIters ? T - j : kSmallRunMaxIters);
+            for (int32_t t = 0; t < chunk; ++t) lr[t] = scheduled_lr(c, c->k + t);
+            const hipError_t e = launch_small_run(c, chunk, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, lr);
+            if (e != hipSuccess) return hip_fail(c, e, "small-problem kernel launch");
+            c->k += chunk;
+            j += chunk;
+        }
+        return GPGA_OK;
+    }
     for (int64_t j = 0; j < T; ++j) {
         gpga_status s = run_grad(c, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, nullptr);
         if (s != GPGA_OK) return s;
@@ -788,6 +804,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "mix_two_pass")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_two_pass must be 0 or 1");
         c->opt_mix_two_pass = (int)value;
+    } else if (!strcmp(name, "small_run")) {
+        if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "small_run must be 0 or 1");
+        c->opt_small_run = (int)value;
     } else if (!strcmp(name, "mix_csr_lds")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_csr_lds must be 0 or 1");
         c->opt_mix_csr_lds = (int)value;

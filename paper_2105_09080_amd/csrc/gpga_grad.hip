@@ -123,6 +123,40 @@ __device__ __forceinline__ double block_sum(double v, double* s_buf) {
     return t;
 }
 
+// Lane-shift reductions on the data-parallel-primitive path of the vector ALU (no LDS
+// round trips): a 64-bit value moved as two 32-bit halves from the lane CTRL selects.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(u & 0xffffffffull), CTRL, 0xf, 0xf, true);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ double readlane_f64(double v, int src_lane) {
+    const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u & 0xffffffffull), src_lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), src_lane);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+// Sum over each aligned row of 16 lanes (shifts by 1, 2, 4, 8 within the row; a lane without
+// a source adds 0); complete in the row's last lane.  Every lane of the wavefront must be active.
+__device__ __forceinline__ double row16_sum_last(double v) {
+    v += dpp_f64<0x111>(v);  // row_shr:1
+    v += dpp_f64<0x112>(v);  // row_shr:2
+    v += dpp_f64<0x114>(v);  // row_shr:4
+    v += dpp_f64<0x118>(v);  // row_shr:8
+    return v;
+}
+// Sum over each aligned group of G lanes, G = 16, 32 or 64 (uniform); complete in the group's
+// last lane.  Every lane of the wavefront must be active.
+__device__ __forceinline__ double group_sum_last(double v, int G) {
+    v = row16_sum_last(v);
+    if (G == 16) return v;
+    const double r0 = readlane_f64(v, 15), r1 = readlane_f64(v, 31), r2 = readlane_f64(v, 47), r3 = readlane_f64(v, 63);
+    if (G == 32) return (threadIdx.x & 32) ? r2 + r3 : r0 + r1;
+    return (r0 + r1) + (r2 + r3);
+}
+
 // Per-sample coefficient and loss term from the margin z.
 //   least squares: r = z - b          coef = r / B           loss = r^2 / (2B)
 //   logistic     : t = y z            coef = -y s(-t) / B    loss = ln(1 + e^{-t}) / B
@@ -359,6 +393,278 @@ __global__ void __launch_bounds__(256) k_virtual_accum(const float* __restrict__
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+
+// ---------------------------------------------------------------- small problems: whole iterations in one workgroup
+
+// When the n x d state and one minibatch of work fit in a single workgroup, T whole
+// iterations of Algorithm 1 - stochastic gradients at the current rows, momentum and local
+// update, gossip step or global average, and the consensus distance - run inside ONE launch
+// with X, M and x^(k+1/2) held in LDS.  Such problems (the logistic simulation of Sec. 5.1:
+// n <= 100 nodes, d = 10) are otherwise bound by the latency of three to five dependent
+// kernel launches per iteration; here an iteration costs a few workgroup barriers and one
+// dependent pair of global reads (sample index, then feature row).
+// The arithmetic follows the large kernels: margins and gradient sums accumulate in fp64,
+// state and x^(k+1/2) are fp32, the mean of a global average is one value broadcast to
+// all rows.
+struct SmallArgs {
+    float* x;  // n x ld, updated in place
+    float* m;  // n x ld momentum buffers (unused when mu = 0)
+    float* g;  // n x ld, receives the gradients of the last iteration
+    int64_t ld;
+    int32_t n, d;
+    const float* feat;  // n x M x d
+    const float* tgt;   // n x M
+    int32_t M;
+    const int32_t* idx;  // T x n x B sample indices, or NULL = every node's whole data set (B = M)
+    int32_t B;
+    int32_t topo;
+    int64_t H, k0;
+    int32_t T;
+    float mu;
+    const int32_t* wptr;  // W in compressed-row form for the sparse-W topologies
+    const int32_t* wcol;
+    const float* wval;
+    double* trace;  // trace[k] = consensus distance after iteration k, for k < trace_cap
+    int64_t trace_cap;
+    float lr[kSmallRunMaxIters];  // step size of each iteration of this launch
+};
+
+template <int KIND, int MOM>
+__global__ void __launch_bounds__(kSmallRunThreads) k_small_run(const SmallArgs a) {
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    const int n = a.n, d = a.d, nd = n * d, B = a.B;
+    double* __restrict__ sMean = reinterpret_cast<double*>(s_raw);  // d column means
+    double* __restrict__ sRed = sMean + d;                          // two sets of one slot per wavefront
+    double* __restrict__ sZ = sRed + 2 * (kSmallRunThreads / kWave);  // n x B margins
+    float* __restrict__ sX = reinterpret_cast<float*>(sZ + n * a.B);
+    float* __restrict__ sY = sX + nd;
+    float* __restrict__ sM = sY + nd;               // MOM only
+    float* __restrict__ sC = sM + (MOM ? nd : 0);   // n x B per-sample coefficients
+    int32_t* __restrict__ sIdx = reinterpret_cast<int32_t*>(sC + n * B);  // n x B sample rows of the iteration
+    const int G = d <= 16 ? 16 : d <= 32 ? 32 : kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6, nw = blockDim.x >> 6;
+    const float invB = 1.0f / (float)B;
+    const float third = 1.0f / 3.0f;
+    int tau = 0;
+    while ((1LL << tau) < n) ++tau;
+    if (tau < 1) tau = 1;
+
+    for (int e = tid; e < nd; e += blockDim.x) {
+        const int i = e / d, c = e - i * d;
+        sX[e] = a.x[(int64_t)i * a.ld + c];
+        if (MOM) sM[e] = a.m[(int64_t)i * a.ld + c];
+    }
+    __syncthreads();
+
+    // column means of src (n x d in LDS) into sMean: one wavefront per column, lanes over rows
+    auto column_means = [&](const float* src) {
+        for (int c = wave; c < d; c += nw) {
+            double s = 0.0;
+            for (int i = lane; i < n; i += kWave) s += (double)src[i * d + c];
+            s = group_sum_last(s, kWave);
+            if (lane == 0) sMean[c] = s / (double)n;
+        }
+        __syncthreads();
+    };
+
+    // Short rows (d <= G) whose pairs fit a few passes are software-pipelined across iterations:
+    // lane lg of group tid / G keeps, for pair p = tid / G + j * PP, the sample row, the label and
+    // feature value number lg of the NEXT iteration in registers.
+    const int npairs = n * B, PP = blockDim.x / G, lg = tid & (G - 1);
+    const bool piped = d <= G && npairs <= kSmallRunPasses * PP;
+    auto fetch_row = [&](int tt, int j) -> int32_t {  // validated sample row of pair j in iteration tt, or -1
+        const int p = tid / G + j * PP;
+        if (tt >= a.T || p >= npairs) return -1;
+        const int32_t r = a.idx ? a.idx[(int64_t)tt * npairs + p] : p % B;
+        return (r >= 0 && r < a.M) ? r : -1;
+    };
+    auto fetch_sample = [&](int j, int32_t r, float& f, float& y) {
+        f = 0.f;
+        y = 0.f;
+        if (r >= 0) {
+            const int i = (tid / G + j * PP) / B;
+            if (lg < d) f = a.feat[((int64_t)i * a.M + r) * d + lg];
+            y = a.tgt[(int64_t)i * a.M + r];
+        }
+    };
+    // The coefficient of a sample needs a double-precision exponential: with one pass of lane
+    // groups the group's last lane computes it on the spot; with several passes the margins
+    // go to LDS first and one thread per pair computes them all at once.
+    const bool one_pass = npairs <= PP;
+    auto coefficient = [&](double z, float y, int32_t r) -> float {
+        float cf = __builtin_nanf(""), ls;  // no valid sample: the node's gradient becomes NaN
+        if (r >= 0) sample_terms<KIND>(z, y, invB, &cf, &ls);
+        return cf;
+    };
+    auto coefficients_from_margins = [&]() {
+        for (int p = tid; p < npairs; p += blockDim.x) sC[p] = coefficient(sZ[p], sC[p], sIdx[p]);
+        __syncthreads();
+    };
+    int32_t rcur[kSmallRunPasses], rnext[kSmallRunPasses];
+    float fcur[kSmallRunPasses], ycur[kSmallRunPasses];
+    if (piped) {
+#pragma unroll
+        for (int j = 0; j < kSmallRunPasses; ++j) {
+            rcur[j] = rnext[j] = -1;
+            fcur[j] = ycur[j] = 0.f;
+            if (j * PP >= npairs) continue;
+            rcur[j] = fetch_row(0, j);
+            fetch_sample(j, rcur[j], fcur[j], ycur[j]);
+            rnext[j] = fetch_row(1, j);
+        }
+    }
+
+    for (int t = 0; t < a.T; ++t) {
+        const int64_t k = a.k0 + t;
+        const float lr = a.lr[t];
+        const int32_t* __restrict__ idx_t = a.idx ? a.idx + (int64_t)t * npairs : nullptr;
+
+        if (piped) {
+            // The rows, labels and feature values of this iteration were fetched during the one
+            // before (they do not depend on x); only the products with the current x are left.
+#pragma unroll
+            for (int j = 0; j < kSmallRunPasses; ++j) {
+                if (j * PP >= npairs) break;  // uniform: no pair left for this pass
+                const int p = tid / G + j * PP;
+                const bool have = p < npairs;
+                const int i = have ? p / B : 0;
+                double acc = (have && rcur[j] >= 0 && lg < d) ? (double)fcur[j] * sX[i * d + lg] : 0.0;
+                acc = group_sum_last(acc, G);
+                if (have && lg == G - 1) {
+                    sIdx[p] = rcur[j];
+                    if (one_pass) {
+                        sC[p] = coefficient(acc, ycur[j], rcur[j]);
+                    } else {  // margin and label now, the coefficient from one thread per pair below
+                        sZ[p] = acc;
+                        sC[p] = ycur[j];
+                    }
+                }
+            }
+            // fetch for the next iteration and the sample rows of the one after it
+#pragma unroll
+            for (int j = 0; j < kSmallRunPasses; ++j) {
+                if (j * PP >= npairs) break;
+                rcur[j] = rnext[j];
+                fetch_sample(j, rcur[j], fcur[j], ycur[j]);
+                rnext[j] = fetch_row(t + 2, j);
+            }
+            __syncthreads();
+            if (!one_pass) coefficients_from_margins();
+        } else {
+            // sample rows of this iteration into LDS (-1 = index outside [0, M))
+            for (int p = tid; p < npairs; p += blockDim.x) {
+                const int32_t r = idx_t ? idx_t[p] : p % B;
+                sIdx[p] = (r >= 0 && r < a.M) ? r : -1;
+            }
+            __syncthreads();
+
+            // per-sample coefficients from the margins <h, x_i>: a group of G lanes per (node,
+            // sample slot), G the power of two that covers d (16..64)
+            for (int p0 = 0; p0 < npairs; p0 += PP) {
+                const int p = p0 + tid / G;
+                const bool have = p < npairs;
+                const int i = have ? p / B : 0;
+                const int32_t r = have ? sIdx[p] : -1;
+                double acc = 0.0;
+                if (r >= 0) {
+                    const float* __restrict__ f = a.feat + ((int64_t)i * a.M + r) * d;
+                    for (int c = lg; c < d; c += G) acc += (double)f[c] * sX[i * d + c];
+                }
+                acc = group_sum_last(acc, G);
+                if (have && lg == G - 1) {
+                    const float y = r >= 0 ? a.tgt[(int64_t)i * a.M + r] : 0.f;
+                    if (one_pass) {
+                        sC[p] = coefficient(acc, y, r);
+                    } else {
+                        sZ[p] = acc;
+                        sC[p] = y;
+                    }
+                }
+            }
+            __syncthreads();
+            if (!one_pass) coefficients_from_margins();
+        }
+
+        // gradient, momentum and local update, one element per thread and pass
+        for (int e = tid; e < nd; e += blockDim.x) {
+            const int i = e / d, c = e - i * d;
+            double acc = 0.0;
+            for (int b = 0; b < B; ++b) {
+                int32_t r = sIdx[i * B + b];
+                if (r < 0) r = 0;  // its coefficient is NaN: row 0 is only a safe address
+                acc += (double)sC[i * B + b] * a.feat[((int64_t)i * a.M + r) * d + c];
+            }
+            const float gv = (float)acc;
+            float mom = gv;
+            if (MOM) {
+                mom = a.mu * sM[e] + gv;
+                sM[e] = mom;
+            }
+            sY[e] = MOM == 2 ? sX[e] - lr * (gv + a.mu * mom) : sX[e] - lr * mom;
+            if (t == a.T - 1) a.g[(int64_t)i * a.ld + c] = gv;
+        }
+        __syncthreads();
+
+        // gossip step or global average (Algorithm 1: the mean iff mod(k+1, H) = 0)
+        const bool global = a.topo == GPGA_TOPO_FULL || (a.H > 0 && (k + 1) % a.H == 0);
+        if (n > 1 && global) column_means(sY);
+        const int S = (int)((1LL << (int)(k % tau)) % n);  // one-peer offset of this iteration
+        for (int e = tid; e < nd; e += blockDim.x) {
+            const int i = e / d, c = e - i * d;
+            float v = sY[e];
+            if (n > 1) {
+                if (global) {
+                    v = (float)sMean[c];
+                } else if (a.topo == GPGA_TOPO_RING) {
+                    const int im = i == 0 ? n - 1 : i - 1, ip = i == n - 1 ? 0 : i + 1;
+                    v = (sY[im * d + c] + v + sY[ip * d + c]) * third;
+                } else if (a.topo == GPGA_TOPO_EXPO1) {
+                    if (S) v = (v + sY[((i + S) % n) * d + c]) * 0.5f;
+                } else if (a.topo != GPGA_TOPO_NONE) {
+                    float acc = 0.f;
+                    for (int p = a.wptr[i]; p < a.wptr[i + 1]; ++p) acc += a.wval[p] * sY[a.wcol[p] * d + c];
+                    v = acc;
+                }
+            }
+            sX[e] = v;
+        }
+        __syncthreads();
+
+        // consensus distance ||X - 1 xbar^T||_F of the new iterates (exactly 0 after an average)
+        if (a.trace && k < a.trace_cap) {
+            double part = 0.0;
+            if (n > 1 && !global) {
+                column_means(sX);
+                for (int e = tid; e < nd; e += blockDim.x) {
+                    const double dv = (double)sX[e] - sMean[e % d];
+                    part += dv * dv;
+                }
+            }
+            part = group_sum_last(part, kWave);
+            double* __restrict__ slots = sRed + (t & 1) * (kSmallRunThreads / kWave);  // the other half next time
+            if (lane == 0) slots[wave] = part;
+            __syncthreads();
+            if (tid == 0) {
+                double tot = 0.0;
+                for (int w = 0; w < nw; ++w) tot += slots[w];
+                a.trace[k] = sqrt(tot);
+            }
+        }
+    }
+
+    for (int e = tid; e < nd; e += blockDim.x) {
+        const int i = e / d, c = e - i * d;
+        a.x[(int64_t)i * a.ld + c] = sX[e];
+        if (MOM) a.m[(int64_t)i * a.ld + c] = sM[e];
+    }
+}
+
+size_t small_run_lds(const gpga_ctx* c, int32_t Beff) {
+    const size_t nd = (size_t)c->n * (size_t)c->d;
+    return ((size_t)c->d + 2 * (kSmallRunThreads / kWave) + (size_t)c->n * (size_t)Beff) * sizeof(double) +
+           ((c->mu != 0.f ? 3 : 2) * nd + 2 * (size_t)c->n * (size_t)Beff) * sizeof(float);
+}
+
 }  // namespace
 
 hipError_t launch_synth_grad(const gpga_ctx* c) {
@@ -440,4 +746,59 @@ hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B,
     hipLaunchKernelGGL((k_virtual_accum<BMAX>), grid2, block, 0, c->stream, coef, idx, B, c->d, k0,
                        k1, c->mu_sigma, vec_ok, c->g, c->ld);
     return hipGetLastError();
+}
+
+bool small_run_fits(const gpga_ctx* c, const int32_t* idx, int32_t B) {
+    if (c->opt_small_run == 0 || c->aga) return false;
+    if (c->problem != PROB_LSQ && c->problem != PROB_LOGREG) return false;
+    if ((c->topo == GPGA_TOPO_GRID || c->topo == GPGA_TOPO_EXPO || c->topo == GPGA_TOPO_CUSTOM) && !c->csr_ready)
+        return false;
+    const int64_t Beff = idx ? B : c->M;
+    if (Beff < 1 || c->d > 4096 || c->n > 4096) return false;
+    const int64_t nd = (int64_t)c->n * c->d, nb = (int64_t)c->n * Beff;
+    // one workgroup does all the work of an iteration: keep it to a few hundred operations per thread
+    if (nd > 8192 || nb > 4096 || nb * c->d > (1 << 17)) return false;
+    return small_run_lds(c, (int32_t)Beff) <= 100 * 1024 && small_run_lds(c, (int32_t)Beff) <= (size_t)c->max_lds_block;
+}
+
+template <int KIND>
+static hipError_t launch_small_kind(const gpga_ctx* c, const SmallArgs& a, size_t lds) {
+    const dim3 grid(1), block(kSmallRunThreads);
+    if (c->mu == 0.f) {
+        hipLaunchKernelGGL((k_small_run<KIND, 0>), grid, block, lds, c->stream, a);
+    } else if (!c->nesterov) {
+        hipLaunchKernelGGL((k_small_run<KIND, 1>), grid, block, lds, c->stream, a);
+    } else {
+        hipLaunchKernelGGL((k_small_run<KIND, 2>), grid, block, lds, c->stream, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_small_run(const gpga_ctx* c, int32_t T, const int32_t* idx, int32_t B, const float* lr) {
+    if (T < 1 || T > kSmallRunMaxIters) return hipErrorInvalidValue;
+    SmallArgs a;
+    a.x = c->x;
+    a.m = c->m;
+    a.g = c->g;
+    a.ld = c->ld;
+    a.n = c->n;
+    a.d = (int32_t)c->d;
+    a.feat = c->feat;
+    a.tgt = c->tgt;
+    a.M = c->M;
+    a.idx = idx;
+    a.B = idx ? B : c->M;
+    a.topo = c->topo;
+    a.H = c->H;
+    a.k0 = c->k;
+    a.T = T;
+    a.mu = c->mu;
+    a.wptr = c->csr_ptr_d;
+    a.wcol = c->csr_col_d;
+    a.wval = c->csr_val_d;
+    a.trace = c->trace;
+    a.trace_cap = c->trace_cap;
+    for (int t = 0; t < T; ++t) a.lr[t] = lr[t];
+    const size_t lds = small_run_lds(c, a.B);
+    return c->problem == PROB_LSQ ? launch_small_kind<PROB_LSQ>(c, a, lds) : launch_small_kind<PROB_LOGREG>(c, a, lds);
 }

@@ -33,6 +33,10 @@ struct HostCsr {
     std::vector<float> val;
 };
 
+constexpr int kSmallRunThreads = 1024;   // workgroup of the single-workgroup trajectory kernel
+constexpr int kSmallRunPasses = 8;     // (node, sample) pairs a lane group keeps in registers for the next iteration
+constexpr int kSmallRunMaxIters = 256;   // iterations per launch (their step sizes travel in the kernel arguments)
+
 enum LrSchedule : int { SCHED_NONE = 0, SCHED_STEP, SCHED_MILESTONES, SCHED_POLY };
 constexpr int kMaxMilestones = 16;
 
@@ -81,6 +85,7 @@ struct gpga_ctx {
     int opt_mix_waves = 0;       // sparse-W tile kernel: wavefronts per workgroup (0 = automatic, 2, 4, 8, 16)
     int opt_mix_two_pass = 0;  // 1 = sparse-W steps always take the two-pass path
     int opt_mix_csr_lds = 1;   // 0 = the tile kernel reads W from global memory even when it fits in LDS
+    int opt_small_run = 1;     // 0 = gpga_run never takes the single-workgroup path for small problems
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
     int num_cus = 256;
     int max_lds_block = 64 * 1024;  // LDS bytes one workgroup may ask for on this device
@@ -164,6 +169,12 @@ double mixing_beta(int32_t n, const HostCsr& w);
 hipError_t launch_synth_grad(const gpga_ctx* c);
 hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
 hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
+// Small problems: T <= kSmallRunMaxIters whole iterations (stored-feature gradients, update,
+// mix or average, consensus trace) in one single-workgroup launch, x updated in place and
+// g left holding the last gradients; lr[t] is the step size of iteration c->k + t.
+// small_run_fits tells whether the context's problem and sizes qualify.
+bool small_run_fits(const gpga_ctx* c, const int32_t* idx, int32_t B);
+hipError_t launch_small_run(const gpga_ctx* c, int32_t T, const int32_t* idx, int32_t B, const float* lr);
 // Column chunks per node of the virtual-feature margin pass; it needs n * B * chunks doubles in c->partials.
 int64_t virtual_margin_chunks(const gpga_ctx* c);
 
