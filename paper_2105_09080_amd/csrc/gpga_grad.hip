@@ -221,6 +221,33 @@ __global__ void __launch_bounds__(256) k_rows_margin(const float* __restrict__ f
     }
 }
 
+// Pass 1 for short rows (d <= 32): one thread per (node, sample slot); neighbouring threads
+// read neighbouring rows, so a full-batch evaluation over many samples streams the
+// feature array instead of spending a workgroup on every ten-element dot product.
+template <int KIND>
+__global__ void __launch_bounds__(256) k_rows_margin_short(const float* __restrict__ feat,
+                                                           const float* __restrict__ tgt,
+                                                           const float* __restrict__ x, int64_t ld,
+                                                           const int32_t* __restrict__ idx, int32_t B,
+                                                           int32_t M, int32_t d, int64_t pairs,
+                                                           float* __restrict__ coef,
+                                                           float* __restrict__ lossterm) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // i * B + b
+    if (p >= pairs) return;
+    const int64_t i = p / B;
+    const int32_t r = idx ? idx[p] : (int32_t)(p - i * B);
+    float cf = __builtin_nanf(""), ls = __builtin_nanf("");  // index outside [0, M): no access, NaN
+    if (r >= 0 && r < M) {
+        const float* __restrict__ f = feat + (i * M + r) * d;
+        const float* __restrict__ xi = x + i * ld;
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) acc += (double)f[c] * xi[c];
+        sample_terms<KIND>(acc, tgt[i * M + r], 1.0f / (float)B, &cf, &ls);
+    }
+    coef[p] = cf;
+    lossterm[p] = ls;
+}
+
 // Pass 2: one lane per column quad of node i: g = sum_b coef_b * row_b[c].
 __global__ void __launch_bounds__(256) k_rows_accum(const float* __restrict__ feat,
                                                     const float* __restrict__ coef,
@@ -684,7 +711,17 @@ hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, fl
     const int vec_feat = aligned16(c->feat) && (c->d % 4 == 0);
     const int vec_x = vec_feat && aligned16(c->x) && (c->ld % 4 == 0);
     dim3 grid1((unsigned)Beff, (unsigned)c->n), block(256);
-    if (c->problem == PROB_LSQ) {
+    const int64_t pairs = (int64_t)c->n * Beff;
+    if (c->d <= 32 && (pairs + 255) / 256 <= 0x7fffffffLL) {
+        const dim3 grid_short((unsigned)((pairs + 255) / 256));
+        if (c->problem == PROB_LSQ) {
+            hipLaunchKernelGGL((k_rows_margin_short<PROB_LSQ>), grid_short, block, 0, c->stream, c->feat, c->tgt,
+                               c->x, c->ld, idx, Beff, c->M, (int32_t)c->d, pairs, coef, lossterm);
+        } else {
+            hipLaunchKernelGGL((k_rows_margin_short<PROB_LOGREG>), grid_short, block, 0, c->stream, c->feat, c->tgt,
+                               c->x, c->ld, idx, Beff, c->M, (int32_t)c->d, pairs, coef, lossterm);
+        }
+    } else if (c->problem == PROB_LSQ) {
         hipLaunchKernelGGL((k_rows_margin<PROB_LSQ>), grid1, block, 0, c->stream, c->feat, c->tgt,
                            c->x, c->ld, idx, Beff, c->M, c->d, vec_x, coef, lossterm);
     } else {

@@ -34,18 +34,27 @@ METHODS = {
 
 class LossProbe:
     """f(xbar) = (1/n) sum_i f_i(xbar) over each node's full local data, evaluated by the
-    library on a second context whose rows are all set to xbar."""
+    library on a second context whose rows are all set to xbar.  A probe only enqueues
+    work (mean, row fill, loss kernels) on the simulation's stream and keeps the n losses
+    on the device; ``values`` waits once and returns every f(xbar) recorded so far."""
 
-    def __init__(self, n, d, feat_dev, y_dev, M, stream):
+    def __init__(self, n, d, feat_dev, y_dev, M, stream, capacity):
         self.sim = Simulation(n, d, topology="none", H=0, lr=0.0, momentum=0.0, stream=stream)
         B.gpga_problem_logreg(self.sim.ctx, feat_dev, y_dev, M)
+        with torch.cuda.stream(stream):
+            self.xbar = torch.empty(d, dtype=torch.float32, device=self.sim.device)
+            self.losses = torch.empty((capacity, n), dtype=torch.float32, device=self.sim.device)
+        self.count = 0
 
-    def __call__(self, run: Simulation) -> float:
-        xbar = run.mean()
-        B.gpga_reset(self.sim.ctx, xbar)
-        losses = self.sim.local_loss(None)
+    def __call__(self, run: Simulation):
+        B.gpga_mean(run.ctx, self.xbar)
+        B.gpga_reset(self.sim.ctx, self.xbar)
+        B.gpga_local_loss(self.sim.ctx, None, 0, self.losses[self.count])
+        self.count += 1
+
+    def values(self) -> np.ndarray:
         self.sim.stream.synchronize()        # the kernels ran on the simulation's stream, not torch's current one
-        return float(losses.cpu().numpy().astype(np.float64).mean())
+        return self.losses[: self.count].cpu().numpy().astype(np.float64).mean(axis=1)
 
     def close(self):
         self.sim.close()
@@ -64,9 +73,10 @@ def run_method(method: str, topology: str, n: int, d: int, feat, y, idx, *, H: i
     B.gpga_lr_schedule_step(sim.ctx, float(np.float32(lr0)), halve_every, 0.5)
     feat_dev, y_dev = sim.problem_logreg(feat, y)
     idx_dev = sim.upload_batches(idx)
-    probe = LossProbe(n, d, feat_dev, y_dev, M, stream)
+    probe = LossProbe(n, d, feat_dev, y_dev, M, stream, capacity=T // eval_every + 2)
     trace = sim.attach_trace(T)
-    losses, at = [probe(sim)], [0]
+    probe(sim)
+    at = [0]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     with torch.cuda.stream(stream):
@@ -76,10 +86,11 @@ def run_method(method: str, topology: str, n: int, d: int, feat, y, idx, *, H: i
             sim.run(chunk, idx_dev[k:k + chunk])          # the loop of Algorithm 1, enqueued by one call
             k += chunk
             if k % eval_every == 0:
-                losses.append(probe(sim))
+                probe(sim)
                 at.append(k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    losses = probe.values()
     out = {"method": method, "topology": topo_override or topology, "n": n, "H": period(H), "iters": T,
            "iters_per_s": T / dt, "beta": sim.beta, "consensus": trace.cpu().numpy().copy(),
            "loss_at": np.asarray(at), "loss": np.asarray(losses), "x_final": sim.X.cpu().numpy()}
