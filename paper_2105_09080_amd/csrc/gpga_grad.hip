@@ -472,6 +472,7 @@ __global__ void __launch_bounds__(kSmallRunThreads) k_small_run(const SmallArgs 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6, nw = blockDim.x >> 6;
     const float invB = 1.0f / (float)B;
     const float third = 1.0f / 3.0f;
+    const double inv_n = 1.0 / (double)n;
     int tau = 0;
     while ((1LL << tau) < n) ++tau;
     if (tau < 1) tau = 1;
@@ -489,7 +490,7 @@ __global__ void __launch_bounds__(kSmallRunThreads) k_small_run(const SmallArgs 
             double s = 0.0;
             for (int i = lane; i < n; i += kWave) s += (double)src[i * d + c];
             s = group_sum_last(s, kWave);
-            if (lane == 0) sMean[c] = s / (double)n;
+            if (lane == 0) sMean[c] = s * inv_n;
         }
         __syncthreads();
     };
@@ -657,14 +658,20 @@ __global__ void __launch_bounds__(kSmallRunThreads) k_small_run(const SmallArgs 
         }
         __syncthreads();
 
-        // consensus distance ||X - 1 xbar^T||_F of the new iterates (exactly 0 after an average)
+        // consensus distance ||X - 1 xbar^T||_F of the new iterates (exactly 0 after an average):
+        // a wavefront takes whole columns, lanes over the rows, so the column mean and the
+        // squared deviations from it need no exchange with other wavefronts
         if (a.trace && k < a.trace_cap) {
             double part = 0.0;
             if (n > 1 && !global) {
-                column_means(sX);
-                for (int e = tid; e < nd; e += blockDim.x) {
-                    const double dv = (double)sX[e] - sMean[e % d];
-                    part += dv * dv;
+                for (int c = wave; c < d; c += nw) {
+                    double s1 = 0.0;
+                    for (int i = lane; i < n; i += kWave) s1 += (double)sX[i * d + c];
+                    const double mean = group_sum_last(s1, kWave) * inv_n;
+                    for (int i = lane; i < n; i += kWave) {
+                        const double dv = (double)sX[i * d + c] - mean;
+                        part += dv * dv;
+                    }
                 }
             }
             part = group_sum_last(part, kWave);
