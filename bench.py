@@ -73,6 +73,8 @@ def parse_args():
     ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1,cfg5:ring",
                     help="comma list of extra workload:topology pairs measured after the primary ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-small", action="store_true",
+                    help="skip the iterations/s measurement on the shape of the paper's logistic simulation")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="run this many plain device copies of one n x d buffer before the timed loop "
                          "(a kernel of known size: reads and writes 4*n*d bytes; used to scale rocprofv3 "
@@ -272,6 +274,34 @@ def run_cfg5_sweep(T):
             torch.cuda.empty_cache()
 
 
+def run_simulation_shape(T=4000):
+    """Iterations/s of the whole loop (gpga_run) on the shape of the paper's logistic simulation
+    (Sec. 5.1: n = 100 nodes, d = 10, one sample per node and iteration, ring, H = 16, consensus
+    trace on), with whole iterations in one workgroup and with one kernel per stage."""
+    import torch
+
+    from paper_2105_09080_amd import harness, inputs
+    n, d, M, B = 100, 10, 8000, 1
+    feat, y, _ = inputs.logreg_simulation_problem(n, d, M, seed=0)
+    idx = inputs.batch_indices(T, n, B, M, seed=0)
+    out = {"workload": f"Sec. 5.1 simulation shape: n={n} d={d} M={M} B={B} ring H=16, trace on", "iterations": T}
+    for key, small in (("single_workgroup_iters_per_s", 1), ("kernel_per_stage_iters_per_s", 0)):
+        sim = harness.Simulation(n, d, topology="ring", H=16, lr=0.2, momentum=0.0)
+        sim.set_option("small_run", small)
+        sim.problem_logreg(feat, y)
+        idx_d = sim.upload_batches(idx)
+        sim.attach_trace(2 * T)
+        sim.run(T, idx_d)
+        torch.cuda.synchronize()
+        sim.set_state(k=0)
+        t0 = time.perf_counter()
+        sim.run(T, idx_d)
+        torch.cuda.synchronize()
+        out[key] = T / (time.perf_counter() - t0)
+        sim.close()
+    return out
+
+
 def cpu_baseline(cfg_name, topology, budget_s=15.0):
     """The oracle as it stands on a column slab of the workload (the recursion is
     column-separable with synthetic gradients), scaled to the full width."""
@@ -381,6 +411,8 @@ def main():
              "grad_ms_avg": r["grad_ms_avg"], "achieved_gbs": r["achieved_gbs"], "frac": r["achieved_gbs"] / HBM_PEAK_GBS,
              "global_step_gbs": r.get("global_gbs"), "consensus_trace": r.get("consensus_trace")} for r in others],
     }
+    if not args.no_small:
+        out["small_problem"] = run_simulation_shape()
     out["paper_context"] = PAPER_CONTEXT
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, topo)
