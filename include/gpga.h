@@ -185,7 +185,7 @@ gpga_status gpga_step(gpga_ctx* ctx);
  * evaluating the minibatch losses itself in the iterations that end in a global
  * average (those synchronise, as gpga_aga_step does).
  * Small problems with stored features (least squares or logistic; n*d <= 8192,
- * n*B <= 4096, n*B*d <= 2^17; the simulation of Sec. 5.1 is one) take a second form
+ * d <= 512, B <= 32, n*B <= 4096, n*B*d <= 2^17; the simulation of Sec. 5.1 is one) take a second form
  * of the same loop unless option "small_run" is 0: whole iterations - gradients,
  * momentum and local update, gossip step or global average, consensus trace - run
  * inside single-workgroup launches of up to 256 iterations with the state in LDS.

@@ -596,7 +596,13 @@ __global__ void __launch_bounds__(kSmallRunThreads) k_small_run(const SmallArgs 
                 double acc = 0.0;
                 if (r >= 0) {
                     const float* __restrict__ f = a.feat + ((int64_t)i * a.M + r) * d;
-                    for (int c = lg; c < d; c += G) acc += (double)f[c] * sX[i * d + c];
+                    int c = lg;
+                    for (; c + 3 * G < d; c += 4 * G) {  // four loads in flight
+                        const float f0 = f[c], f1 = f[c + G], f2 = f[c + 2 * G], f3 = f[c + 3 * G];
+                        acc += (double)f0 * sX[i * d + c] + (double)f1 * sX[i * d + c + G] +
+                               (double)f2 * sX[i * d + c + 2 * G] + (double)f3 * sX[i * d + c + 3 * G];
+                    }
+                    for (; c < d; c += G) acc += (double)f[c] * sX[i * d + c];
                 }
                 acc = group_sum_last(acc, G);
                 if (have && lg == G - 1) {
@@ -798,7 +804,7 @@ bool small_run_fits(const gpga_ctx* c, const int32_t* idx, int32_t B) {
     if ((c->topo == GPGA_TOPO_GRID || c->topo == GPGA_TOPO_EXPO || c->topo == GPGA_TOPO_CUSTOM) && !c->csr_ready)
         return false;
     const int64_t Beff = idx ? B : c->M;
-    if (Beff < 1 || c->d > 4096 || c->n > 4096) return false;
+    if (Beff < 1 || Beff > 32 || c->d > 512 || c->n > 4096) return false;  // a thread walks a row / a batch: keep both short
     const int64_t nd = (int64_t)c->n * c->d, nb = (int64_t)c->n * Beff;
     // one workgroup does all the work of an iteration: keep it to a few hundred operations per thread
     if (nd > 8192 || nb > 4096 || nb * c->d > (1 << 17)) return false;

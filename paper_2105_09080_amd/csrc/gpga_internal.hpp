@@ -34,7 +34,7 @@ struct HostCsr {
 };
 
 constexpr int kSmallRunThreads = 1024;   // workgroup of the single-workgroup trajectory kernel
-constexpr int kSmallRunPasses = 8;     // (node, sample) pairs a lane group keeps in registers for the next iteration
+constexpr int kSmallRunPasses = 4;     // (node, sample) pairs a lane group keeps in registers for the next iteration
 constexpr int kSmallRunMaxIters = 256;   // iterations per launch (their step sizes travel in the kernel arguments)
 
 enum LrSchedule : int { SCHED_NONE = 0, SCHED_STEP, SCHED_MILESTONES, SCHED_POLY };
