@@ -536,9 +536,9 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
         ge.ncols = pass == 0 ? nv : tail;
         if (ge.ncols == 0) continue;
         const int v = pass == 0 ? 4 : 1;
-        const bool fuse = trace && !global && !csr && tail == 0;
+        const bool fuse = trace && !global && tail == 0;
         e = global ? launch_step_global(c, ge, v)
-                   : csr ? launch_step_csr(c, ge, v)
+                   : csr ? launch_step_csr(c, ge, v, fuse ? c->partials + 1 : nullptr, fuse ? &spread_count : nullptr)
                          : launch_step_walk(c, ge, mode, S, v, fuse ? c->partials + 1 : nullptr,
                                             fuse ? &spread_count : nullptr);
     }

@@ -151,7 +151,10 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec);
 // Gossip step with a sparse W in CSR form (c->csr_*_d): one fused kernel with the
 // column tile of all n rows staged in LDS when it fits, else local update into
 // the g buffer followed by a sparse product.
-hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec);
+// With spread_partials / spread_count (as for launch_step_walk) the fused kernel also leaves one
+// partial sum of squared deviations per column tile when it runs with 16-byte lanes.
+hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, double* spread_partials = nullptr,
+                           int64_t* spread_count = nullptr);
 
 // Host-side graph construction and analysis.
 void build_ring_csr(int32_t n, HostCsr* out);

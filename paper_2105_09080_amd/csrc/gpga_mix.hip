@@ -19,8 +19,11 @@
 //    pass 2 is the sparse product x_new = W y with workgroups ordered so that
 //    all rows of a column tile run together and re-reads of y hit the caches
 //    (28 B per element of HBM traffic when they do).
+#include <type_traits>
+
 #include "gpga_internal.hpp"
 #include "gpga_pace.hpp"
+#include "gpga_spread.hpp"
 
 namespace {
 
@@ -51,6 +54,7 @@ struct TileArgs {
     CsrDev w;
     int64_t tiles;  // column tiles; workgroups stride over them
     int32_t nnz;    // entries of W (the LDS copy needs the count)
+    double* spread_partials;  // TRACE kernels: one sum of squared deviations per column tile
     PaceArgs pace;
 };
 
@@ -60,12 +64,42 @@ constexpr int kTileUnroll = 4;
 constexpr size_t kTileLdsBytes = 64 * 1024;
 constexpr size_t kTileCsrLdsBytes = 16 * 1024;  // largest W copied into LDS (two workgroups per CU still fit)
 
+// Per-lane spread sums of one wavefront to LDS (stride kWave doubles between the 8 values) ...
+__device__ __forceinline__ void tile_spread_store(const ColumnSpread<v4f>& sp, double* dst) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        dst[(size_t)j * kWave] = sp.s1[j];
+        dst[(size_t)(4 + j) * kWave] = sp.s2[j];
+    }
+}
+__device__ __forceinline__ void tile_spread_store(const ColumnSpread<v2f>&, double*) {}
+__device__ __forceinline__ void tile_spread_store(const ColumnSpread<float>&, double*) {}
+// ... and this lane's four columns finished from the sums of all `waves` wavefronts.
+template <typename T>
+__device__ __forceinline__ double tile_spread_finish(const double* src, int waves, double inv_n) {
+    double r = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        double s1 = 0.0, s2 = 0.0;
+        for (int w = 0; w < waves; ++w) {
+            s1 += src[((size_t)w * 8 + j) * kWave];
+            s2 += src[((size_t)w * 8 + 4 + j) * kWave];
+        }
+        const double v = s2 - s1 * s1 * inv_n;
+        r += v > 0.0 ? v : 0.0;
+    }
+    return r;
+}
+
 // LCSR: W is copied into LDS behind the tile once per workgroup and phase 2 reads it from
 // there.  Vector memory operations of a wavefront retire in order, so a neighbour list
 // fetched from global memory inside the output loop would make every output row wait for
 // the stores of the rows before it; LDS reads are counted separately and leave the stores
 // streaming.
-template <typename T, int MOM, bool LCSR>
+// TRACE (16-byte lanes only): the kernel also leaves, per column tile, the sum over its columns
+// of sum_i (x_new[i] - column mean)^2: every wavefront keeps shifted fp64 sums of the rows it
+// stores, the wavefronts' sums meet in LDS once the tile's y is no longer needed.
+template <typename T, int MOM, bool LCSR, bool TRACE>
 __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     extern __shared__ __align__(16) unsigned char s_raw[];
@@ -186,6 +220,8 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
         int cj_next;
         float wv_next;
         fetch_list(wave, 0, cj_next, wv_next);
+        ColumnSpread<T> spread;
+        if (TRACE) spread.reset(sy[lane]);  // row 0 of y: a value near every x_new of the column
         for (int i = wave; i < n; i += kTileWaves) {
             const int cnt = LCSR ? __builtin_amdgcn_readfirstlane(s_ptr[i + 1] - s_ptr[i]) : a.w.ptr[i + 1] - a.w.ptr[i];
             int cj_l = cj_next;
@@ -207,8 +243,24 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
             pace_wait(a.pace, t0, units_done);
             units_done += 1u;
             if (on) st_stream(xnp + (int64_t)i * ldT, acc);
+            if (TRACE) spread.add(acc);  // lanes without a column hold zeros throughout
         }
         __syncthreads();  // the next tile's phase 1 overwrites the staged y
+        if (TRACE) {
+            // the wavefronts' sums meet in LDS ([wave][8][lane] doubles over the y tile, which is
+            // no longer needed); wavefront 0 adds them in wavefront order, finishes the columns
+            // and leaves one partial for the tile
+            double* __restrict__ sw = reinterpret_cast<double*>(s_raw);
+            tile_spread_store(spread, sw + ((size_t)wave * 8) * kWave + lane);
+            __syncthreads();
+            if (wave == 0) {
+                double part = tile_spread_finish<T>(sw + lane, kTileWaves, 1.0 / (double)n);
+#pragma unroll
+                for (int off = kWave / 2; off > 0; off >>= 1) part += __shfl_down(part, off, kWave);
+                if (lane == 0) a.spread_partials[tile] = part;
+            }
+            __syncthreads();
+        }
     }
 }
 
@@ -246,7 +298,7 @@ __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, 
 }
 
 
-template <typename T, int MOM, bool LCSR>
+template <typename T, int MOM, bool LCSR, bool TRACE>
 hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds) {
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
@@ -261,38 +313,55 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
     const int want = c->opt_blocks_per_cu < 0 ? (gbs > 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
     if (want > 0) {
         int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM, LCSR>, threads, lds) != hipSuccess || occ < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM, LCSR, TRACE>, threads, lds) != hipSuccess || occ < 1)
             occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
         if (resident < blocks) blocks = resident;
         pace_setup(const_cast<gpga_ctx*>(c), gbs, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
-    hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
+    hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR, TRACE>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
     return hipGetLastError();
 }
 
+template <typename T, bool TRACE>
+hipError_t launch_tile_traced(const gpga_ctx* c, const TileArgs& a, int waves, size_t lds, bool lcsr, int mom) {
+    if (lcsr) {
+        if (mom == 2) return launch_tile_mom<T, 2, true, TRACE>(c, a, waves, lds);
+        return mom == 1 ? launch_tile_mom<T, 1, true, TRACE>(c, a, waves, lds) : launch_tile_mom<T, 0, true, TRACE>(c, a, waves, lds);
+    }
+    if (mom == 2) return launch_tile_mom<T, 2, false, TRACE>(c, a, waves, lds);
+    return mom == 1 ? launch_tile_mom<T, 1, false, TRACE>(c, a, waves, lds) : launch_tile_mom<T, 0, false, TRACE>(c, a, waves, lds);
+}
+
 template <typename T>
-hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom) {
+hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom,
+                       double* spread_partials = nullptr, int64_t* spread_count = nullptr) {
     TileArgs a;
     a.ge = ge;
     a.w = w;
     a.tiles = (ge.ncols + kWave - 1) / kWave;
+    a.spread_partials = nullptr;
     if (a.tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.nnz = (int32_t)c->csr.col.size();
     const size_t tile_lds = (size_t)ge.n * kWave * sizeof(T);
     // W rides along in LDS when it is small and the device grants the workgroup the room
     const size_t csr_lds = ((((size_t)ge.n + 2) & ~(size_t)1) + 2 * (size_t)a.nnz) * sizeof(int32_t);
     const bool lcsr = c->opt_mix_csr_lds != 0 && csr_lds <= kTileCsrLdsBytes && tile_lds + csr_lds <= (size_t)c->max_lds_block;
-    const size_t lds = tile_lds + (lcsr ? csr_lds : 0);
     // measured on the n = 64, d = 25.6M shape: 8 or 16 wavefronts per workgroup stream
     // 5.2-6.0 TB/s, 4 wavefronts 4.8-5.1 TB/s (more rows are in flight while others mix)
     const int waves = c->opt_mix_waves ? c->opt_mix_waves : (ge.n >= 32 ? 8 : kTileWavesDefault);
-    if (lcsr) {
-        if (mom == 2) return launch_tile_mom<T, 2, true>(c, a, waves, lds);
-        return mom == 1 ? launch_tile_mom<T, 1, true>(c, a, waves, lds) : launch_tile_mom<T, 0, true>(c, a, waves, lds);
+    size_t lds = tile_lds + (lcsr ? csr_lds : 0);
+    if constexpr (std::is_same<T, v4f>::value) if (spread_partials && spread_count) {
+        // the consensus sums ride along: the wavefronts' sums need waves x 8 x 64 doubles of LDS
+        const size_t meet = (size_t)waves * 8 * kWave * sizeof(double);
+        size_t tile_part = tile_lds < meet ? meet : tile_lds;
+        if (tile_part + (lcsr ? csr_lds : 0) <= (size_t)c->max_lds_block && tile_part == tile_lds) {
+            a.spread_partials = spread_partials;
+            *spread_count = a.tiles;
+            return launch_tile_traced<T, true>(c, a, waves, lds, lcsr, mom);
+        }
     }
-    if (mom == 2) return launch_tile_mom<T, 2, false>(c, a, waves, lds);
-    return mom == 1 ? launch_tile_mom<T, 1, false>(c, a, waves, lds) : launch_tile_mom<T, 0, false>(c, a, waves, lds);
+    return launch_tile_traced<T, false>(c, a, waves, lds, lcsr, mom);
 }
 
 template <typename T>
@@ -309,7 +378,9 @@ hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& 
 
 }  // namespace
 
-hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec) {
+hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, double* spread_partials,
+                           int64_t* spread_count) {
+    if (spread_count) *spread_count = 0;
     if (ge.ncols <= 0) return hipSuccess;
     if (!c->csr_ready) return hipErrorInvalidValue;
     const CsrDev w{c->csr_ptr_d, c->csr_col_d, c->csr_val_d};
@@ -322,7 +393,7 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec) {
         // satisfy the narrower types)
         StepGeom g2 = ge;
         if (!two_pass && lane_cap >= 16 && n * kWave * sizeof(v4f) <= kTileLdsBytes)
-            return launch_tile<v4f>(c, ge, w, mom);
+            return launch_tile<v4f>(c, ge, w, mom, spread_partials, spread_count);
         if (!two_pass && lane_cap >= 8 && n * kWave * sizeof(v2f) <= kTileLdsBytes) {
             g2.ncols = ge.ncols * 2;
             return launch_tile<v2f>(c, g2, w, mom);

@@ -40,6 +40,7 @@
 
 #include "gpga_internal.hpp"
 #include "gpga_pace.hpp"
+#include "gpga_spread.hpp"
 
 namespace {
 
@@ -88,43 +89,6 @@ __device__ __forceinline__ T half_step(const T& xv, const T& gv, const T& mom, f
 // the first row, set by the caller before the first add), deviations
 // formed in fp32 (exact or nearly so while rows are close), sums in fp64, so
 // that sum_i (x_i - xbar)^2 = S2 - S1^2 / n keeps the small quantity.
-template <typename T>
-struct ColumnSpread;
-template <>
-struct ColumnSpread<v4f> {
-    v4f ref;
-    double s1[4], s2[4];
-    __device__ __forceinline__ void reset(const v4f& r) {
-        ref = r;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s1[j] = s2[j] = 0.0;
-    }
-    __device__ __forceinline__ void add(const v4f& v) {  // branch-free: it sits in the pipelined loop
-        const v4f dl = v - ref;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const double t = (double)dl[j];
-            s1[j] += t;
-            s2[j] += t * t;
-        }
-    }
-    __device__ __forceinline__ double sum_sq(double inv_n) const {
-        double r = 0.0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const double v = s2[j] - s1[j] * s1[j] * inv_n;
-            r += v > 0.0 ? v : 0.0;
-        }
-        return r;
-    }
-};
-template <>
-struct ColumnSpread<float> {  // never instantiated with tracing on; keeps the template uniform
-    __device__ __forceinline__ void reset(float) {}
-    __device__ __forceinline__ void add(float) {}
-    __device__ __forceinline__ double sum_sq(double) const { return 0.0; }
-};
-
 constexpr int kMaxWaves = 8;
 constexpr int kDefaultUnroll = 2;  // rows per batch; two batches are in flight (software pipeline)
 

@@ -36,7 +36,14 @@ CASES = [
     (64, 600_000, "expo1", 6, 0.9, 8, {"blocks_per_cu": 4, "pace_gbs": 9000, "unroll": 2}),
     (24, 600_000, "expo1", 0, 0.9, 6, {"blocks_per_cu": 2, "pace_gbs": 4000}),   # n not a power of two
     (16, 1003, "ring", 5, 0.9, 6, {}),                        # ragged d: scalar tail -> reduction pass
-    (20, 2000, "grid", 4, 0.9, 6, {}),                        # sparse W
+    (20, 2000, "grid", 4, 0.9, 6, {}),                        # sparse W, tile kernel: sums ride along
+    (64, 300_004, "grid", 6, 0.9, 7, {}),
+    (64, 300_004, "expo", 0, 0.9, 4, {"blocks_per_cu": 2}),   # workgroups striding over several tiles
+    (64, 100_000, "grid", 0, 0.0, 3, {"mix_waves": 16}),      # 16 wavefronts' sums fill the whole tile
+    (32, 100_000, "expo", 0, 0.9, 3, {"mix_waves": 16}),      # ... and do not fit here: reduction pass
+    (12, 2000, "expo", 0, 0.9, 4, {}),                        # tile smaller than the sums: reduction pass
+    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8}),  # narrow lanes: reduction pass
+    (300, 2000, "grid", 5, 0.9, 6, {}),                       # two-pass sparse W: reduction pass
     (12, 500, "none", 3, 0.5, 5, {}),
 ]
 
