@@ -238,6 +238,19 @@ int64_t gpga_period(const gpga_ctx* ctx);
  * Synchronises the stream; *out_host is a host double. */
 gpga_status gpga_consensus_error(gpga_ctx* ctx, double* out_host);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same quantity as
+ * gpga_consensus_error, from the same kernels, written as one double to out_dev (a
+ * DEVICE pointer, 8-byte aligned, caller-owned) on the bound stream.  The call
+ * allocates and frees nothing and does not synchronise: the per-workgroup partial sums
+ * live in a static device array of 1 MiB (131072 doubles) that every GPU the library runs
+ * on holds until the process ends.  Limit: one partial per 1024 columns on 16-byte
+ * aligned rows with ld % 4 == 0 (d <= 134 216 704), per 256 columns otherwise
+ * (d <= 33 554 432); a larger d gives EINVAL with the limit in gpga_last_error.  All
+ * calls on one GPU share that GPU's array: calls that overlap there (other streams or
+ * threads) race; calls queued on one stream do not.  ESTATE before gpga_bind. */
+gpga_status gpga_consensus_error_static(gpga_ctx* ctx, double* out_dev);
+
 /* Consensus trace without host synchronisation.  While a trace is attached, every
  * gpga_step / gpga_aga_step that completes iteration k < capacity also enqueues
  * trace_dev[k] = ||X^(k+1) - 1 xbar^T||_F (a double on the DEVICE, caller-owned,

@@ -60,6 +60,7 @@ SIGNATURES = [
     ("gpga_aga_step", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_period", _c.c_int64, [_ctx_p]),
     ("gpga_consensus_error", _c.c_int, [_ctx_p, _c.POINTER(_c.c_double)]),
+    ("gpga_consensus_error_static", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_set_trace", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int64]),
     ("gpga_mean", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_current_x", _c.c_int, [_ctx_p, _c.POINTER(_c.c_void_p)]),
@@ -261,6 +262,11 @@ def gpga_consensus_error(ctx) -> float:
     out = ctypes.c_double()
     _check(ctx, _lib.gpga_consensus_error(ctx, ctypes.byref(out)))
     return out.value
+
+
+def gpga_consensus_error_static(ctx, out):
+    """out: float64 CUDA tensor (or address) receiving the consensus distance; nothing is allocated."""
+    _check(ctx, _lib.gpga_consensus_error_static(ctx, _ptr(out)))
 
 
 def gpga_set_trace(ctx, trace, capacity: int = 0):

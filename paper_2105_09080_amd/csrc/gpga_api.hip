@@ -282,6 +282,10 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
     } else {
         c->pace_slots = nullptr;  // launches simply run unpaced
     }
+    {   // set-up of gpga_consensus_error_static on this device, so that its calls find the address ready
+        double* static_ptr = nullptr;
+        (void)static_scratch_for_device(c->device, &static_ptr);
+    }
     if (hipHostMalloc(reinterpret_cast<void**>(&c->host_scalar), sizeof(double), hipHostMallocDefault) !=
         hipSuccess) {
         c->host_scalar = nullptr;

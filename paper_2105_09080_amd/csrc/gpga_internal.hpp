@@ -187,8 +187,16 @@ hipError_t launch_col_mean(const gpga_ctx* c, float* xbar);
 // Sum of squared deviations into c->partials[0] (device double).
 hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed);
 size_t consensus_partials_needed(const gpga_ctx* c);
+// Partials the reduction pass over the bound X really writes (depends on its alignment).
+size_t consensus_partials_used(const gpga_ctx* c);
 // slot[0] = consensus distance of the live X (reduction pass + one final kernel).
 hipError_t launch_consensus_trace(gpga_ctx* c, double* slot);
+// The same with the per-workgroup partials in caller-chosen scratch (scratch_cap doubles, at least
+// consensus_partials_needed(c) - 1): slot[0] = ||X - 1 xbar^T||_F.  hipErrorOutOfMemory if too small.
+hipError_t launch_consensus_distance(const gpga_ctx* c, double* scratch, size_t scratch_cap, double* slot);
+// Entries of the static scratch array behind gpga_consensus_error_static and its per-device address.
+size_t static_scratch_doubles();
+hipError_t static_scratch_for_device(int device, double** ptr_out);
 // slot[0] = sqrt(sum of `count` partials) (count = 0 stores 0): one entry of the consensus trace.
 hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot);
 // Streaming probe over count16 16-byte words (kind 0 read, 1 write, 2 copy, 3 three reads : two writes).

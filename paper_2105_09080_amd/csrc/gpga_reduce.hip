@@ -237,6 +237,12 @@ hipError_t launch_probe_stream(int kind, const float* src, float* dst, const flo
     return hipGetLastError();
 }
 
+size_t consensus_partials_used(const gpga_ctx* c) {
+    const bool vec = aligned16(c->x) && (c->ld % 4 == 0);
+    const int64_t nv = vec ? c->d / 4 : 0;
+    return (size_t)((nv + 255) / 256 + (c->d - nv * 4 + 255) / 256);
+}
+
 size_t consensus_partials_needed(const gpga_ctx* c) {
     // vector pass workgroups + scalar tail workgroup + 1 result slot
     return (size_t)((c->d / 4 + 255) / 256) + (size_t)((c->d + 255) / 256) + 2;
@@ -272,16 +278,15 @@ hipError_t launch_col_mean(const gpga_ctx* c, float* xbar) {
     return hipGetLastError();
 }
 
-// Per-workgroup partial sums of squared deviations of the live X into c->partials[1 ..];
-// *count receives their number.
-static hipError_t launch_consensus_partials(gpga_ctx* c, int64_t* count) {
+// Per-workgroup partial sums of squared deviations of the live X into parts[0 ..] (room for
+// `cap` doubles); *count receives their number.
+static hipError_t launch_consensus_partials(const gpga_ctx* c, double* parts, size_t cap, int64_t* count) {
     *count = 0;
-    if (c->partials_cap < consensus_partials_needed(c)) return hipErrorOutOfMemory;
     const bool vec = aligned16(c->x) && (c->ld % 4 == 0);
     const int64_t nv = vec ? c->d / 4 : 0;
     const int64_t tail = c->d - nv * 4;
     const int64_t b1 = (nv + 255) / 256, b2 = (tail + 255) / 256;
-    double* parts = c->partials + 1;  // slot 0 holds the result of the synchronous entry point
+    if ((size_t)(b1 + b2) > cap) return hipErrorOutOfMemory;
     if (b1 > 0) {
         hipLaunchKernelGGL((k_consensus<v4f>), dim3((unsigned)b1), dim3(256), 0, c->stream, c->x,
                            c->ld, (int64_t)0, nv, c->n, parts);
@@ -297,17 +302,22 @@ static hipError_t launch_consensus_partials(gpga_ctx* c, int64_t* count) {
 hipError_t launch_consensus_sq(gpga_ctx* c, size_t* partials_needed) {
     *partials_needed = consensus_partials_needed(c);
     int64_t count = 0;
-    const hipError_t e = launch_consensus_partials(c, &count);
+    // slot 0 of the context's scratch holds the result of the synchronous entry point
+    const hipError_t e = launch_consensus_partials(c, c->partials + 1, c->partials_cap - 1, &count);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(256), 0, c->stream, c->partials + 1, count, c->partials);
     return hipGetLastError();
 }
 
 hipError_t launch_consensus_trace(gpga_ctx* c, double* slot) {
+    return launch_consensus_distance(c, c->partials + 1, c->partials_cap - 1, slot);
+}
+
+hipError_t launch_consensus_distance(const gpga_ctx* c, double* scratch, size_t scratch_cap, double* slot) {
     int64_t count = 0;
-    const hipError_t e = launch_consensus_partials(c, &count);
+    const hipError_t e = launch_consensus_partials(c, scratch, scratch_cap, &count);
     if (e != hipSuccess) return e;
-    return launch_trace_store(c, c->partials + 1, count, slot);
+    return launch_trace_store(c, scratch, count, slot);
 }
 
 hipError_t launch_trace_store(const gpga_ctx* c, const double* partials, int64_t count, double* slot) {

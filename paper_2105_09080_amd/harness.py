@@ -156,6 +156,10 @@ class Simulation:
     def consensus_error(self) -> float:
         return B.gpga_consensus_error(self.ctx)
 
+    def consensus_error_static(self, out: torch.Tensor):
+        """Consensus distance into ``out`` (one float64 on the device), asynchronously, no allocation."""
+        B.gpga_consensus_error_static(self.ctx, out)
+
     def attach_trace(self, capacity: int) -> torch.Tensor:
         """Device array that receives the consensus distance after every step (no host sync)."""
         self.trace = torch.full((capacity,), float("nan"), dtype=torch.float64, device=self.device)
