@@ -31,10 +31,12 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 # HBM bytes per launch of the fused gossip step measured with rocprofv3 --pmc
 # (FETCH_SIZE run + WRITE_SIZE run, scaled by a copy kernel of known size); the
 # summaries live under profiles/.  None = not measured for that workload.
+# These are constants copied from those summaries, NOT something a bench run measures: the JSON line
+# carries them as `traffic` together with `traffic_source`.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3/ring": 32768370216,    # profiles/step_walk_cfg3_ring.md: 12.000 B fetched + 8.000 B written per element
-    "cfg4/expo1": 140803063107,  # profiles/step_cfg4_expo1.md (k_step_walk, all five offsets)
-    "cfg3/grid": 32768074151,    # profiles/step_tile_cfg3_grid.md (k_step_tile)
+    "cfg3/ring": (32768370216, "profiles/step_walk_cfg3_ring.md"),     # 12.000 B fetched + 8.000 B written per element
+    "cfg4/expo1": (140803063107, "profiles/step_cfg4_expo1.md"),       # k_step_walk, all five offsets
+    "cfg3/grid": (32768074151, "profiles/step_tile_cfg3_grid.md"),     # k_step_tile
 }
 
 
@@ -94,6 +96,23 @@ def parse_args():
     return ap.parse_args()
 
 
+def window_start(H, T, steps):
+    """First iteration of the timed window.  A run of at least H steps (or a workload that never
+    averages) starts at iteration 0 as the workload states.  A shorter run times the LAST `steps`
+    iterations of the first averaging period, steps H - steps .. H - 1, so that the window ends with
+    a global-average step and (for windows of at least 8 steps of the one-peer graph with 6 offsets)
+    still holds every offset: the offset whose turn coincides with the averaging step shows up one
+    cycle of offsets earlier."""
+    if H <= 0 or steps >= H:
+        return 0
+    return H - steps
+
+
+def one_peer_offset(n, k):
+    tau = max(1, (n - 1).bit_length())
+    return (1 << (k % tau)) % n
+
+
 def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1):
     """Times `steps` passes of local_grad + step.  Returns a dict of measurements."""
     import torch
@@ -113,24 +132,31 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     else:  # cfg5: virtual-feature logistic regression
         y = inputs.virtual_labels(n, c["M"], c["seed"])
         sim.problem_logreg_virtual(c["seed"], y, c["mu_var"])
-        idx = sim.upload_batches(inputs.batch_indices(steps + warmup, n, c["B"], c["M"], c["seed"]))
+        idx = sim.upload_batches(inputs.batch_indices(max(c["H"], 0) + steps + warmup, n, c["B"], c["M"], c["seed"]))
         grad = lambda: sim.local_grad(idx[sim.k])
 
     want_trace = (cfg_name == "cfg5") if trace < 0 else bool(trace)
-    trace_dev = sim.attach_trace(steps + warmup) if want_trace else None
+    k_first = window_start(c["H"], c["T"], steps)
+    k_warm = max(0, k_first - warmup)
+    trace_dev = sim.attach_trace(k_first + steps + warmup) if want_trace else None
     with torch.cuda.stream(stream):
         for _ in range(copy_probe):
             sim._bufs[1].copy_(sim._bufs[0])
+        # the iteration counter (which drives the averaging schedule, the one-peer offset and the address
+        # of the synthetic gradients) is placed like on a resume: warm-up iterations lead up to the window
+        sim.set_state(k=k_warm)
         for _ in range(warmup):
             grad()
             sim.step()
+        sim.set_state(k=k_first)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-        kinds = []
+        kinds, offsets = [], []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
             k = sim.k
             kinds.append("global" if (c["H"] > 0 and (k + 1) % c["H"] == 0) else "gossip")
+            offsets.append(one_peer_offset(n, k) if topology == "expo1" else None)
             ev[i][0].record()
             grad()
             ev[i][1].record()
@@ -143,8 +169,14 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     gossip = [t for t, kd in zip(step_ms, kinds) if kd == "gossip"]
     glob = [t for t, kd in zip(step_ms, kinds) if kd == "global"]
     elts = n * d
+    per_offset = {}
+    for t, kd, off in zip(step_ms, kinds, offsets):
+        if kd == "gossip" and off is not None:
+            per_offset.setdefault(off, []).append(t)
     res = {
         "workload": f"{cfg_name}: n={n} d={d} {topology} H={c['H']} momentum={c['momentum']}",
+        "cfg": cfg_name, "iterations": [k_first, k_first + steps - 1],
+        "gossip_ms_by_offset": {str(o): sum(v) / len(v) for o, v in sorted(per_offset.items())} or None,
         "n": n, "d": d, "topology": topology, "H": c["H"],
         "wall_s": t1 - t0,
         "ms_per_step": 1e3 * (t1 - t0) / steps,
@@ -166,6 +198,7 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     res["consensus_error_final"] = sim.consensus_error()
     if trace_dev is not None:
         tr = trace_dev.cpu().numpy()
+        tr = tr[tr == tr]          # entries of the iterations that ran (the rest is still NaN)
         res["consensus_trace"] = {"steps": int(len(tr)), "first": [float(v) for v in tr[:10]],
                                   "last": float(tr[-1]), "max": float(tr.max())}
     sim.close()
@@ -302,9 +335,13 @@ def run_simulation_shape(T=4000):
     return out
 
 
-def cpu_baseline(cfg_name, topology, budget_s=15.0):
-    """The oracle as it stands on a column slab of the workload (the recursion is
-    column-separable with synthetic gradients), scaled to the full width."""
+def cpu_baseline(cfg_name, topology, budget_s=16.0):
+    """The oracle as it stands on a column slab of the workload (the recursion is column-separable
+    with synthetic gradients), scaled to the full width.  Two legs of about budget_s / 2 each: the
+    whole path (the oracle's counter-RNG gradients + its step), which is what `value` measures on
+    the GPU, and the step alone on prescribed gradients.  `cores` is what the timed code really kept
+    busy: process CPU time / wall time (NumPy's elementwise work and the oracle's generator run on
+    one thread, only the W @ Y product uses the BLAS pool)."""
     import numpy as np
     from threadpoolctl import threadpool_info
 
@@ -315,24 +352,33 @@ def cpu_baseline(cfg_name, topology, budget_s=15.0):
     n, d = c["n"], c["d"]
     slab = 65536
     cols = np.arange(slab)
-    ref = orc.GossipPGA(n, slab, topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"], storage="f32")
-    t0 = time.perf_counter()
-    steps = 0
-    while True:
-        G = orc.synthetic_grad(c["seed"], steps, n, cols, c["grad_var"])
-        ref.step(G)
-        steps += 1
-        if time.perf_counter() - t0 > budget_s or steps >= c["T"]:
-            break
-    dt = (time.perf_counter() - t0) / steps
-    full_step_s = dt * d / slab
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    kw = dict(topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"], storage="f32")
+
+    def timed(make_grad):
+        ref = orc.GossipPGA(n, slab, **kw)
+        w0, p0, steps = time.perf_counter(), time.process_time(), 0
+        while True:
+            ref.step(make_grad(steps))
+            steps += 1
+            if time.perf_counter() - w0 > budget_s / 2 or steps >= c["T"]:
+                break
+        wall, cpu = time.perf_counter() - w0, time.process_time() - p0
+        return steps, wall / steps, cpu / wall
+
+    steps_a, dt_a, busy_a = timed(lambda k: orc.synthetic_grad(c["seed"], k, n, cols, c["grad_var"]))
+    G_fixed = orc.synthetic_grad(c["seed"], 0, n, cols, c["grad_var"])
+    steps_b, dt_b, busy_b = timed(lambda k: G_fixed)
+    blas = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    scale = d / slab
     return {
-        "value": 1.0 / full_step_s, "unit": "steps/s", "cores": threads, "kind": "oracle",
-        "sample": f"{steps} steps of the NumPy float64 oracle (gradient generation + step) on a {n}x{slab} "
-                  f"column slab of {cfg_name}/{topology}; {dt:.3f} s per slab step, scaled by d/slab = {d / slab:.1f} "
-                  f"(columns are independent); BLAS threads {threads} of {os.cpu_count()} host CPUs, "
-                  f"the counter-RNG part is single-threaded NumPy",
+        "value": 1.0 / (dt_a * scale), "unit": "steps/s", "cores": max(1, round(busy_a)), "kind": "oracle",
+        "step_only_value": 1.0 / (dt_b * scale), "step_only_cores": max(1, round(busy_b)),
+        "busy_threads_measured": {"whole_path": busy_a, "step_only": busy_b},
+        "blas_pool_threads": blas, "host_cpus": os.cpu_count(),
+        "sample": f"NumPy float64 oracle on a {n}x{slab} column slab of {cfg_name}/{topology}, scaled by d/slab = {scale:.1f} "
+                  f"(columns are independent): whole path (counter-RNG gradients + step) {steps_a} steps at {dt_a:.3f} s per "
+                  f"slab step keeping {busy_a:.1f} threads busy; step alone on prescribed gradients {steps_b} steps at "
+                  f"{dt_b:.4f} s keeping {busy_b:.1f} threads busy (BLAS pool {blas} threads, used by W @ Y only)",
     }
 
 
@@ -370,6 +416,31 @@ def main():
         steps = min(args.steps, inputs.CONFIGS[name]["T"])
         others.append(run_workload(name, tp, steps, args.warmup, opts, trace=args.trace))
 
+    def roofline_block(r):
+        key = f"{r['cfg']}/{r['topology']}"
+        traffic, source = MEASURED_TRAFFIC_BYTES.get(key, (None, None))
+        dom_gossip = r["dominant"] == "gossip"
+        return {
+            "bound": "hbm",
+            "workload": r["workload"],
+            "kernel": f"fused gossip step ({gossip_kernel_name(r['topology'], r['n'])})"
+                      if dom_gossip else "fused global-average step (k_step_global)",
+            "achieved": r["achieved_gbs"],
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": r["achieved_gbs"] / HBM_PEAK_GBS,
+            "traffic": traffic,
+            "traffic_source": (f"{source}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the same command, copied from that "
+                               "summary, not measured by this run") if source else None,
+            "algorithmic_bytes_per_launch": r["algorithmic_bytes_per_launch"],
+            "avg_launch_ms": r["gossip_ms_avg"] if dom_gossip else r["global_ms_avg"],
+            "gossip_ms_by_one_peer_offset": r["gossip_ms_by_offset"],
+            "global_step_avg_ms": r["global_ms_avg"],
+            "global_step_gbs": r.get("global_gbs"),
+            "global_step_frac": r["global_gbs"] / HBM_PEAK_GBS if r.get("global_gbs") else None,
+            "iterations_timed": r["iterations"], "n_gossip": r["n_gossip"], "n_global": r["n_global"],
+        }
+
     out = {
         "metric": "Gossip-PGA steps/s and achieved HBM GB/s (% of peak) for fused n x d step",
         "value": main_res["steps_per_s"],
@@ -384,29 +455,19 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": main_res["workload"], "options": opts,
+                   "iterations_timed": main_res["iterations"],
                    "step": "gpga_local_grad (counter-RNG gradients) + gpga_step (fused update + mix/average)"},
         "node_updates_per_s": main_res["steps_per_s"] * main_res["n"],
         "step_only_steps_per_s": main_res["step_only_steps_per_s"],
-        "roofline": {
-            "bound": "hbm",
-            "kernel": f"fused gossip step ({gossip_kernel_name(topo, main_res['n'])})"
-                      if main_res["dominant"] == "gossip" else "fused global-average step (k_step_global)",
-            "achieved": main_res["achieved_gbs"],
-            "peak": HBM_PEAK_GBS,
-            "unit": "GB/s",
-            "frac": main_res["achieved_gbs"] / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(f"{args.config}/{topo}"),
-            "algorithmic_bytes_per_launch": main_res["algorithmic_bytes_per_launch"],
-            "avg_launch_ms": main_res["gossip_ms_avg"] if main_res["dominant"] == "gossip" else main_res["global_ms_avg"],
-            "global_step_avg_ms": main_res["global_ms_avg"],
-            "global_step_gbs": main_res.get("global_gbs"),
-        },
+        "roofline": roofline_block(main_res),
+        "rooflines_other_workloads": {f"{r['cfg']}/{r['topology']}": roofline_block(r) for r in others},
         "consensus_trace": main_res.get("consensus_trace"),
         "breakdown": {"grad_ms_avg": main_res["grad_ms_avg"], "step_ms_avg": main_res["step_ms_avg"],
                       "grad_write_gbs": main_res["grad_write_gbs"],
                       "n_gossip": main_res["n_gossip"], "n_global": main_res["n_global"]},
         "other_workloads": [
             {"workload": r["workload"], "steps_per_s": r["steps_per_s"], "step_only_steps_per_s": r["step_only_steps_per_s"],
+             "node_updates_per_s": r["steps_per_s"] * r["n"],
              "ms_per_step": r["ms_per_step"], "gossip_ms_avg": r["gossip_ms_avg"], "global_ms_avg": r["global_ms_avg"],
              "grad_ms_avg": r["grad_ms_avg"], "achieved_gbs": r["achieved_gbs"], "frac": r["achieved_gbs"] / HBM_PEAK_GBS,
              "global_step_gbs": r.get("global_gbs"), "consensus_trace": r.get("consensus_trace")} for r in others],
