@@ -117,6 +117,7 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     """Times `steps` passes of local_grad + step.  Returns a dict of measurements."""
     import torch
 
+    from paper_2105_09080_amd import binding as B
     from paper_2105_09080_amd import inputs
     from paper_2105_09080_amd.harness import Simulation
 
@@ -142,6 +143,10 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     with torch.cuda.stream(stream):
         for _ in range(copy_probe):
             sim._bufs[1].copy_(sim._bufs[0])
+        # persistent launches find their pacing rate by themselves, a dozen launches per kind of step:
+        # let that happen before the W warm-up steps, then start again from x0 = 0
+        sim.tune(32)
+        B.gpga_reset(sim.ctx, None)
         # the iteration counter (which drives the averaging schedule, the one-peer offset and the address
         # of the synthetic gradients) is placed like on a resume: warm-up iterations lead up to the window
         sim.set_state(k=k_warm)
@@ -185,7 +190,7 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
         "step_ms_avg": sum(step_ms) / steps,
         "gossip_ms_avg": sum(gossip) / len(gossip) if gossip else None,
         "global_ms_avg": sum(glob) / len(glob) if glob else None,
-        "n_gossip": len(gossip), "n_global": len(glob),
+        "n_gossip": len(gossip), "n_global": len(glob), "step_ms_each": step_ms,
         "algorithmic_bytes_per_launch": BYTES_PER_ELT * elts,
     }
     dom = res["gossip_ms_avg"] if gossip else res["global_ms_avg"]
@@ -196,6 +201,16 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     res["grad_write_gbs"] = 4 * elts / (res["grad_ms_avg"] * 1e-3) / 1e9
     res["step_only_steps_per_s"] = 1e3 / res["step_ms_avg"]
     res["consensus_error_final"] = sim.consensus_error()
+    # where the pacing controllers of the persistent launches ended up (device-side state, read back once)
+    res["pace_controllers"] = {}
+    for kind in [k + d for k in ("ring", "global", "peer_long", "peer_16", "peer_8", "peer_4", "cycles") for d in ("", "/1")]:
+        launches = sim.query(f"pace_launches:{kind}")
+        if launches > 0:
+            res["pace_controllers"][kind] = {
+                "rate_gbs": round(sim.query(f"pace_rate_gbs:{kind}")), "launches": int(launches),
+                "late_launches": int(sim.query(f"pace_late_launches:{kind}")),
+                "last_late_us": round(sim.query(f"pace_last_late_us:{kind}"), 1),
+                "last_plan_us": round(sim.query(f"pace_last_plan_us:{kind}"), 1)}
     if trace_dev is not None:
         tr = trace_dev.cpu().numpy()
         tr = tr[tr == tr]          # entries of the iterations that ran (the rest is still NaN)
@@ -439,6 +454,8 @@ def main():
             "global_step_gbs": r.get("global_gbs"),
             "global_step_frac": r["global_gbs"] / HBM_PEAK_GBS if r.get("global_gbs") else None,
             "iterations_timed": r["iterations"], "n_gossip": r["n_gossip"], "n_global": r["n_global"],
+            "pace_controllers": r["pace_controllers"],
+            "step_ms_each": [round(t, 3) for t in r["step_ms_each"]],
         }
 
     out = {

@@ -285,12 +285,35 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * "pace_min_cycle" (shortest row cycle whose walk is paced, 0 = automatic (4)),
  * "blocks_per_cu" (persistent launch of the fused step: -1 = automatic, 0 = one
  * workgroup per column-tile group, k = 1..32 resident workgroups per compute unit,
- * each striding over the tile groups), "pace_gbs" (target rate in GB/s of paced
- * persistent launches: -1 = automatic, 0 = free running; paced wavefronts issue
+ * each striding over the tile groups), "pace_gbs" (rate in GB/s of paced
+ * persistent launches: -1 = automatic: every kind of launch finds its own rate, each
+ * launch measuring how far its wavefronts fell behind and setting the rate of the
+ * next; 0 = free running; > 0 = exactly this rate; paced wavefronts issue
  * each row batch no earlier than a common start time plus the time the whole
  * launch needs for the rows before it at that rate, which keeps the chip
  * streaming a few rows at a time). */
 gpga_status gpga_set_option(gpga_ctx* ctx, const char* name, int64_t value);
+
+/* Lets the pacing controllers settle before a measurement or a latency-critical phase.
+ * Large problems run the fused step as persistent launches paced at a rate that every
+ * kind of launch (gossip step per one-peer offset class, global average) finds for itself,
+ * each launch setting the rate of the next; a controller needs about a dozen launches.
+ * gpga_tune runs `launches` (1..4096) fused steps of every kind the context's schedule
+ * contains on the bound buffers.  The iteration counter is restored; the CONTENTS of x,
+ * x_new and m afterwards are unspecified (call gpga_reset or set them), g is only read.
+ * Does nothing when the launches of this context are not paced.  Asynchronous. */
+gpga_status gpga_tune(gpga_ctx* ctx, int32_t launches);
+
+/* Read-only facts about the context as doubles.  Names:
+ *   "pace_<field>:<kind>" and "pace_<field>:<kind>/1"  state of the pacing controller of one kind
+ *       of persistent launch, for steps that read the array bound as x (no suffix) or the one
+ *       bound as x_new ("/1"): the two directions of the ping-pong have controllers of their own
+ *       (kind: global, ring, peer_long, peer_16, peer_8, peer_4, cycles, self, tile; field: rate_gbs =
+ *       rate of the next launch, last_rate_gbs, last_late_us = how long after its last
+ *       deadline the slowest wavefront of the most recent launch ended, last_plan_us,
+ *       last_elapsed_us, launches, late_launches, hold).  Synchronises the stream.
+ * EINVAL for an unknown name. */
+gpga_status gpga_query(gpga_ctx* ctx, const char* name, double* value_out);
 
 /* Measurement aid, not part of the method: a plain streaming kernel over `bytes`
  * (a multiple of 16) per array of device memory on hip_stream, with the same 128-bit

@@ -65,6 +65,8 @@ SIGNATURES = [
     ("gpga_mean", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_current_x", _c.c_int, [_ctx_p, _c.POINTER(_c.c_void_p)]),
     ("gpga_set_option", _c.c_int, [_ctx_p, _c.c_char_p, _c.c_int64]),
+    ("gpga_tune", _c.c_int, [_ctx_p, _c.c_int32]),
+    ("gpga_query", _c.c_int, [_ctx_p, _c.c_char_p, _c.POINTER(_c.c_double)]),
     ("gpga_probe_stream", _c.c_int, [_c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64,
                                      _c.c_int32, _c.c_void_p]),
     ("gpga_last_error", _c.c_char_p, [_ctx_p]),
@@ -286,6 +288,16 @@ def gpga_current_x(ctx) -> int:
 
 def gpga_set_option(ctx, name: str, value: int):
     _check(ctx, _lib.gpga_set_option(ctx, name.encode(), value))
+
+
+def gpga_tune(ctx, launches: int):
+    _check(ctx, _lib.gpga_tune(ctx, launches))
+
+
+def gpga_query(ctx, name: str) -> float:
+    out = ctypes.c_double()
+    _check(ctx, _lib.gpga_query(ctx, name.encode(), ctypes.byref(out)))
+    return out.value
 
 
 def gpga_probe_stream(kind: int, src, dst, nbytes: int, stream=None, src2=None, inout=None, blocks_per_cu: int = 0):

@@ -9,6 +9,7 @@
 #include <new>
 
 #include "gpga_internal.hpp"
+#include "gpga_pace.hpp"
 
 namespace {
 
@@ -276,11 +277,11 @@ gpga_status gpga_create(gpga_ctx** out, int32_t n, int64_t d, int32_t topology, 
         return GPGA_ENOMEM;
     }
     c->partials_cap = need;
-    if (hipMalloc(reinterpret_cast<void**>(&c->pace_slots), 64 * sizeof(unsigned long long)) == hipSuccess) {
-        (void)hipMemset(c->pace_slots, 0, 64 * sizeof(unsigned long long));
+    if (hipMalloc(reinterpret_cast<void**>(&c->pace_states), kPaceKeys * sizeof(PaceState)) == hipSuccess) {
+        (void)hipMemset(c->pace_states, 0, kPaceKeys * sizeof(PaceState));
         (void)hipDeviceSynchronize();
     } else {
-        c->pace_slots = nullptr;  // launches simply run unpaced
+        c->pace_states = nullptr;  // launches simply run unpaced
     }
     {   // set-up of gpga_consensus_error_static on this device, so that its calls find the address ready
         double* static_ptr = nullptr;
@@ -311,7 +312,7 @@ gpga_status gpga_destroy(gpga_ctx* c) {
     if (c->coef) (void)hipFree(c->coef);
     if (c->aga_loss) (void)hipFree(c->aga_loss);
     if (c->partials) (void)hipFree(c->partials);
-    if (c->pace_slots) (void)hipFree(c->pace_slots);
+    if (c->pace_states) (void)hipFree(c->pace_states);
     free_csr_device(c);
     if (c->host_scalar) (void)hipHostFree(c->host_scalar);
     delete c;
@@ -339,6 +340,7 @@ gpga_status gpga_bind(gpga_ctx* c, float* x, float* x_new, float* m, float* g, i
             }
     }
     c->x = x;
+    c->x_first = x;
     c->x_new = x_new;
     c->m = m;
     c->g = g;
@@ -853,6 +855,73 @@ gpga_status gpga_probe_stream(int32_t kind, const float* src_dev, float* dst_dev
                                              kind == 0 ? dst_dev : nullptr, blocks,
                                              static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? GPGA_OK : GPGA_EDEVICE;
+}
+
+gpga_status gpga_tune(gpga_ctx* c, int32_t launches) {
+    if (!c) return GPGA_EINVAL;
+    if (launches < 1 || launches > 4096) return fail(c, GPGA_EINVAL, "launches must be 1..4096");
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    if (c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is enabled");
+    DeviceGuard guard(c->device);
+    // only launches large enough to be paced have a rate to find
+    if (!c->pace_states || c->opt_pace_gbs >= 0 || (int64_t)c->n * c->d * 4 < (256ll << 20) || is_csr_topology(c->topo))
+        return GPGA_OK;
+    const int64_t k_saved = c->k;
+    double* const trace_saved = c->trace;
+    c->trace = nullptr;
+    gpga_status s = GPGA_OK;
+    // every kind of step of the schedule: the gossip step at each one-peer offset, the global average
+    const int kinds = c->topo == GPGA_TOPO_EXPO1 ? tau_of(c->n) : 1;
+    for (int kind = 0; kind <= kinds && s == GPGA_OK; ++kind) {
+        const bool global = kind == kinds;
+        if (global && c->H == 0 && c->topo != GPGA_TOPO_FULL) break;
+        if (!global && c->topo == GPGA_TOPO_FULL) continue;
+        for (int32_t j = 0; j < launches && s == GPGA_OK; ++j) {
+            c->k = kind;  // the offset of a one-peer step follows k mod tau
+            s = run_step(c, global);
+        }
+    }
+    c->k = k_saved;
+    c->trace = trace_saved;
+    return s;
+}
+
+gpga_status gpga_query(gpga_ctx* c, const char* name, double* value_out) {
+    if (!c) return GPGA_EINVAL;
+    if (!name || !value_out) return fail(c, GPGA_EINVAL, "name and value_out must not be NULL");
+    if (!strncmp(name, "pace_", 5)) {
+        // "pace_<field>:<kind>[/1]": state of the pacing controller of one kind of launch, for steps that read
+        // the array bound as x (no suffix) or the one bound as x_new ("/1")
+        const char* colon = strchr(name, ':');
+        static const char* kinds[] = {"global", "ring", "peer_long", "peer_8", "peer_4", "cycles", "self", "tile", "peer_16"};
+        int key = -1;
+        for (int j = 0; colon && j < 9; ++j) {
+            const size_t kl = strlen(kinds[j]);
+            if (!strncmp(colon + 1, kinds[j], kl) && (colon[1 + kl] == 0 || !strcmp(colon + 1 + kl, "/1")))
+                key = 2 * j + (colon[1 + kl] ? 1 : 0);
+        }
+        if (key < 0) return fail(c, GPGA_EINVAL, "unknown pacing kind in '%s'", name);
+        if (!c->pace_states) return fail(c, GPGA_ESTATE, "this context has no pacing state");
+        DeviceGuard guard(c->device);
+        PaceState st;
+        hipError_t e = c->bound ? hipStreamSynchronize(c->stream) : hipSuccess;
+        if (e == hipSuccess) e = hipMemcpy(&st, c->pace_states + key, sizeof(st), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return hip_fail(c, e, "pacing state read-back");
+        const double gbs_per_fp = 1.0 / pace_fp_per_gbs(c), us = 1e6 / c->clock_hz;
+        const size_t len = (size_t)(colon - name);
+        auto is = [&](const char* f) { return strlen(f) == len && !strncmp(name, f, len); };
+        if (is("pace_rate_gbs")) *value_out = st.rate_fp * gbs_per_fp;
+        else if (is("pace_last_rate_gbs")) *value_out = st.last_rate_fp * gbs_per_fp;
+        else if (is("pace_launches")) *value_out = st.launches;
+        else if (is("pace_late_launches")) *value_out = st.late_launches;
+        else if (is("pace_last_late_us")) *value_out = st.last_late * us;
+        else if (is("pace_last_plan_us")) *value_out = st.last_plan * us;
+        else if (is("pace_last_elapsed_us")) *value_out = st.last_elapsed * us;
+        else if (is("pace_hold")) *value_out = st.hold;
+        else return fail(c, GPGA_EINVAL, "unknown pacing field in '%s'", name);
+        return GPGA_OK;
+    }
+    return fail(c, GPGA_EINVAL, "unknown query '%s'", name);
 }
 
 const char* gpga_last_error(const gpga_ctx* c) { return c ? c->err : "null context"; }

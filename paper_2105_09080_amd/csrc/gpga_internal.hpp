@@ -40,6 +40,8 @@ constexpr int kSmallRunMaxIters = 256;   // iterations per launch (their step si
 enum LrSchedule : int { SCHED_NONE = 0, SCHED_STEP, SCHED_MILESTONES, SCHED_POLY };
 constexpr int kMaxMilestones = 16;
 
+struct PaceState;  // gpga_pace.hpp
+
 struct gpga_ctx {
     int32_t n = 0;
     int64_t d = 0;
@@ -53,6 +55,7 @@ struct gpga_ctx {
     // bound buffers (borrowed)
     float* x = nullptr;      // live iterates
     float* x_new = nullptr;  // target of the next step
+    const float* x_first = nullptr;  // the array bound as x (tells the two directions of the ping-pong apart)
     float* m = nullptr;
     float* g = nullptr;
     int64_t ld = 0;
@@ -92,9 +95,8 @@ struct gpga_ctx {
     int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
     int opt_cycle_kernel = -1;   // whole-cycle kernel for one-peer cycles of 2 / 4 rows: -1 automatic, 0 never, 1 always
     int opt_pace_min_cycle = 0;  // shortest row cycle that is paced (0 = automatic)
-    uint32_t pace_seq = 0;   // sequence number of paced launches
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
-    unsigned long long* pace_slots = nullptr;  // 64 device words, library-owned
+    PaceState* pace_states = nullptr;  // kPaceKeys controller states in device memory, library-owned
 
     // sparse mixing matrix of the grid / static exponential / custom graphs
     HostCsr csr;                 // host copy (also used by the beta estimate)

@@ -123,7 +123,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
     const int64_t ldT = a.ge.ld / V;
     const float lr = a.ge.lr, mu = a.ge.mu;
     constexpr uint32_t kLoadUnits = MOM ? 4u : 2u;  // 4-byte streams per row in phase 1 (reads + the m store)
-    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    const PaceRun run = pace_begin(a.pace, lane);
     uint32_t units_done = 0;
 
     // Workgroups stride over the column tiles (one tile each in the default one-shot launch).
@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
         if ((tile + 1) * kWave <= a.ge.ncols) {  // every lane has a column
             for (; base + (kTileUnroll - 1) * kTileWaves < n; base += kTileWaves * kTileUnroll) {
                 T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
-                pace_wait(a.pace, t0, units_done);
+                pace_wait(run, units_done);
                 units_done += kTileUnroll * kLoadUnits;
 #pragma unroll
                 for (int u = 0; u < kTileUnroll; ++u) {
@@ -170,7 +170,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
         // Ragged row groups and the last, partial tile: predicated per row and per lane.
         for (; base < n; base += kTileWaves * kTileUnroll) {
             T xv[kTileUnroll], mv[kTileUnroll], gv[kTileUnroll];
-            pace_wait(a.pace, t0, units_done);
+            pace_wait(run, units_done);
             units_done += kTileUnroll * kLoadUnits;
 #pragma unroll
             for (int u = 0; u < kTileUnroll; ++u) {
@@ -240,7 +240,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
                     }
                 }
             }
-            pace_wait(a.pace, t0, units_done);
+            pace_wait(run, units_done);
             units_done += 1u;
             if (on) st_stream(xnp + (int64_t)i * ldT, acc);
             if (TRACE) spread.add(acc);  // lanes without a column hold zeros throughout
@@ -262,6 +262,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
             __syncthreads();
         }
     }
+    pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
 }
 
 // Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  One workgroup = one row of one
@@ -302,9 +303,7 @@ template <typename T, int MOM, bool LCSR, bool TRACE>
 hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds) {
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
-    a.pace.unit_fp = 0;
-    a.pace.slots = nullptr;
-    a.pace.seq = 0;
+    pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
     // Default: one workgroup per tile.  On request ("pace_gbs" / "blocks_per_cu" options) exactly
     // the resident workgroups, striding over the tiles and paced.  Measured on the n = 64,
     // d = 25.6M shape the paced form is bimodal (5.0-5.1 TB/s at most targets, 5.5-5.7 TB/s at
@@ -317,7 +316,7 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
             occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
         if (resident < blocks) blocks = resident;
-        pace_setup(const_cast<gpga_ctx*>(c), gbs, (double)blocks * waves, (int)sizeof(T), &a.pace);
+        pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_TILE, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
     hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR, TRACE>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
     return hipGetLastError();

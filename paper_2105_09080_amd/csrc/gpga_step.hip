@@ -145,7 +145,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
     const float third = 1.0f / 3.0f;
     constexpr uint32_t kRowUnits = MOM ? 5u : 3u;  // 4-byte streams touched per row
 
-    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    const PaceRun run = pace_begin(a.pace, lane);
     uint32_t units_done = 0;
 
     // Grid-stride over work items (walker group, tile group), tile group
@@ -220,7 +220,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             int rw[U];
         };
         auto load_full = [&](Batch& b) {
-            pace_wait(a.pace, t0, units_done);
+            pace_wait(run, units_done);
             units_done += U * kRowUnits;
 #pragma unroll
             for (int u = 0; u < U; ++u) load_row(b.xv[u], b.mv[u], b.gv[u], b.rw[u]);
@@ -235,7 +235,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             {
                 T x0, m0, g0, x1, m1, g1;
                 int r0 = 0, r1 = 0;
-                pace_wait(a.pace, t0, units_done);
+                pace_wait(run, units_done);
                 units_done += (len >= 2 ? 2u : 1u) * kRowUnits;
                 load_row(x0, m0, g0, r0);
                 if (len >= 2) load_row(x1, m1, g1, r1);
@@ -326,6 +326,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
         }
         }  // cycles of this work item
     }
+    const unsigned long long t_done = pace_now(a.pace);
     if (TRACE) {
         // one partial per workgroup, summed in a fixed order
         double v = spread_acc;
@@ -339,14 +340,18 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
             a.spread_partials[blockIdx.x] = t;
         }
     }
+    pace_end(a.pace, run, units_done, lane, t_done);
 }
 
-// One-peer steps whose cycles are short (instantiated for 2 rows: offset n/2).  A batch is one
-// whole cycle: its L rows are loaded, turned into y, and every row's pair average
-// (y_j + y_{j+1 mod L}) / 2 is stored; nothing is carried from one batch to the next, so the
-// loop over the C cycles of a column tile is a plain software pipeline (the next cycle's
-// loads are issued ahead of this cycle's stores) and the launch can be persistent and
-// paced like the long walks: the whole chip then streams the same L rows at a time.
+// One-peer steps whose cycles are short (instantiated for L = 2, 4, 8 and 16 rows: offsets n/2 ... n/16).
+// A lane streams the rows of its column group cycle after cycle - rows c, c+S, ..., c+(L-1)S of
+// cycle c, then cycle c+1 - as ONE software pipeline: one row per batch, the loads of the next row
+// (which may belong to the next cycle) issued ahead of this row's stores, two rows in flight
+// throughout.  Only the stencil restarts at a cycle boundary: the first y of a cycle is kept to
+// close it, (y_{L-1} + y_0) / 2, when its last row arrives.  The general walk kernel drains its
+// pipeline at the end of every cycle; with 4-row cycles that exposed one memory latency per four
+// rows and its wavefronts fell behind the pacing clock 5 % earlier than on long cycles.
+// The body is unrolled over the L rows of a cycle, so the loop over cycles is branch-free.
 struct CycleArgs {
     StepGeom ge;
     int32_t S;   // row offset of the peer
@@ -358,6 +363,7 @@ struct CycleArgs {
 
 template <int MOM, int L, bool TRACE = false>
 __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArgs a) {
+    static_assert(L >= 2 && L % 2 == 0, "two row buffers alternate: a cycle has an even number of rows");
     typedef v4f T;
     __shared__ double s_spread[kMaxWaves];
     ColumnSpread<T> spread;
@@ -370,7 +376,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArg
     const int64_t ldT = a.ge.ld / 4;
     const float lr = a.ge.lr, mu = a.ge.mu;
     constexpr uint32_t kRowUnits = MOM ? 5u : 3u;
-    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    const PaceRun run = pace_begin(a.pace, lane);
     uint32_t units_done = 0;
 
     for (int64_t w = blockIdx.x; w < a.gx; w += gridDim.x) {
@@ -382,66 +388,81 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArg
         T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
         T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
 
-        struct Batch {
-            T xv[L], mv[L], gv[L];
-            int rw[L];
+        struct Row {
+            T xv, mv, gv;
+            int rw;
         };
-        auto load_cycle = [&](Batch& b, int cyc) {
-            pace_wait(a.pace, t0, units_done);
-            units_done += L * kRowUnits;
-            int row = cyc;
-#pragma unroll
-            for (int j = 0; j < L; ++j) {
-                b.rw[j] = row;
-                const int64_t off = (int64_t)row * ldT;
-                b.xv[j] = ld_stream(xp + off);
-                if (MOM) b.mv[j] = ld_stream(mp + off);
-                b.gv[j] = ld_stream(gp + off);
-                row += S;
-                if (row >= n) row -= n;
+        int next_row = 0;  // row the next load takes: walks cycle 0, then cycle 1, ...
+        int next_pos = 0, next_cyc = 0;
+        auto load_row = [&](Row& b) {
+            pace_wait(run, units_done);
+            units_done += kRowUnits;
+            b.rw = next_row;
+            const int64_t off = (int64_t)next_row * ldT;
+            b.xv = ld_stream(xp + off);
+            if (MOM) b.mv = ld_stream(mp + off);
+            b.gv = ld_stream(gp + off);
+            if (++next_pos == L) {  // on to the first row of the next cycle
+                next_pos = 0;
+                next_row = ++next_cyc;
+            } else {
+                next_row += S;
+                if (next_row >= n) next_row -= n;
             }
         };
-        auto store_cycle = [&](const Batch& b) {
-            T y[L];
-#pragma unroll
-            for (int j = 0; j < L; ++j) {
-                T mom = b.gv[j];
-                if (MOM) {
-                    mom = mu * b.mv[j] + b.gv[j];
-                    st_stream(mp + (int64_t)b.rw[j] * ldT, mom);
-                }
-                y[j] = half_step<MOM>(b.xv[j], b.gv[j], mom, lr, mu);
+        T yf = T(0), pc = T(0);
+        int row_prev = 0;
+        auto process = [&](const Row& b, int pos) {  // pos is a compile-time constant at every call
+            T mom = b.gv;
+            if (MOM) {
+                mom = mu * b.mv + b.gv;
+                st_stream(mp + (int64_t)b.rw * ldT, mom);
             }
-#pragma unroll
-            for (int j = 0; j < L; ++j) {
-                const T v = (y[j] + y[(j + 1) % L]) * 0.5f;
-                st_stream(xnp + (int64_t)b.rw[j] * ldT, v);
+            const T y = half_step<MOM>(b.xv, b.gv, mom, lr, mu);
+            if (pos == 0) {
+                yf = y;
+            } else {
+                const T v = (pc + y) * 0.5f;
+                st_stream(xnp + (int64_t)row_prev * ldT, v);
                 if (TRACE) spread.add(v);
             }
+            if (pos == L - 1) {
+                const T v = (y + yf) * 0.5f;
+                st_stream(xnp + (int64_t)b.rw * ldT, v);
+                if (TRACE) spread.add(v);
+            }
+            pc = y;
+            row_prev = b.rw;
         };
-        Batch A, B;
-        load_cycle(A, 0);
-        int c = 0;
-        for (; c + 3 <= a.C; c += 2) {
-            load_cycle(B, c + 1);
-            __builtin_amdgcn_sched_barrier(0);  // keep the issue order: loads, then stores
-            store_cycle(A);
-            __builtin_amdgcn_sched_barrier(0);
-            load_cycle(A, c + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            store_cycle(B);
-            __builtin_amdgcn_sched_barrier(0);
+        Row A, B;
+        load_row(A);
+        for (int c = 0; c + 1 < a.C; ++c) {  // every cycle but the last: the load after its last row opens the next cycle
+#pragma unroll
+            for (int pos = 0; pos < L; pos += 2) {
+                load_row(B);
+                __builtin_amdgcn_sched_barrier(0);  // keep the issue order: loads, then stores
+                process(A, pos);
+                __builtin_amdgcn_sched_barrier(0);
+                load_row(A);
+                __builtin_amdgcn_sched_barrier(0);
+                process(B, pos + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (a.C - c == 2) {
-            load_cycle(B, c + 1);
+#pragma unroll
+        for (int pos = 0; pos < L; pos += 2) {  // the last cycle: nothing to load after its last row
+            load_row(B);
             __builtin_amdgcn_sched_barrier(0);
-            store_cycle(A);
-            store_cycle(B);
-        } else {
-            store_cycle(A);
+            process(A, pos);
+            __builtin_amdgcn_sched_barrier(0);
+            if (pos + 2 < L) load_row(A);
+            __builtin_amdgcn_sched_barrier(0);
+            process(B, pos + 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (TRACE) spread_acc += spread.sum_sq(1.0 / (double)n);
     }
+    const unsigned long long t_done = pace_now(a.pace);
     if (TRACE) {
         double v = spread_acc;
 #pragma unroll
@@ -454,6 +475,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_cycles(const CycleArg
             a.spread_partials[blockIdx.x] = t;
         }
     }
+    pace_end(a.pace, run, units_done, lane, t_done);
 }
 
 struct GlobalArgs {
@@ -486,7 +508,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     const int64_t ldT = a.ge.ld / V;  // row stride in units of T
     const float lr = a.ge.lr, mu = a.ge.mu;
     constexpr uint32_t kReadUnits = MOM ? 4u : 2u;  // 4-byte streams per row in the read phase
-    const unsigned long long t0 = pace_begin(a.pace, lane, blockIdx.x == 0 && threadIdx.x == 0);
+    const PaceRun run = pace_begin(a.pace, lane);
     uint32_t units_done = 0;
 
     // deferred mean of the previous whole tile of this wavefront (see below)
@@ -495,7 +517,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
     bool have_prev = false;  // wave-uniform
     auto flush_prev = [&]() {
         for (int row = 0; row < n; row += U) {
-            pace_wait(a.pace, t0, units_done);
+            pace_wait(run, units_done);
             units_done += U;
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -532,7 +554,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
                 constexpr uint32_t kUnits = kReadUnits + (WP ? 1u : 0u);
                 int row = 0;
                 auto load_full = [&](Batch& b) {
-                    pace_wait(a.pace, t0, units_done);
+                    pace_wait(run, units_done);
                     units_done += U * kUnits;
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -612,7 +634,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         if (on) {
             for (int base = r0; base < n; base += RS * U) {
                 T xv[U], mv[U], gv[U];
-                pace_wait(a.pace, t0, units_done);
+                pace_wait(run, units_done);
                 units_done += U * kReadUnits;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -658,7 +680,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         const T mean = sum * a.inv_n;
         if (on) {
             for (int base = r0; base < n; base += RS * U) {
-                pace_wait(a.pace, t0, units_done);
+                pace_wait(run, units_done);
                 units_done += U;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -669,6 +691,7 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_global(const GlobalAr
         }
     }
     if (have_prev) flush_prev();
+    pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
 }
 
 int gcd_i(int a, int b) {
@@ -699,7 +722,8 @@ struct LaunchPlan {
     int bpc = 0;             // requested resident workgroups per CU (0 = one-shot launch)
     int num_cus = 0;
     int waves = 0;           // wavefronts per workgroup
-    double pace_gbs = 0.0;   // target rate of a paced launch (0 = free running)
+    double pace_gbs = 0.0;   // 0 = free running, > 0 = paced at this rate, < 0 = paced at the rate the controller finds
+    int pace_key = 0;        // which controller state the launch shares (PaceKey)
     double clock_hz = 1e8;
     int vec = 4;
     const gpga_ctx* ctx = nullptr;
@@ -710,23 +734,46 @@ template <typename Args, typename Kernel>
 hipError_t launch_planned(Kernel kernel, LaunchPlan plan, Args a, hipStream_t st) {
     const int threads = kWave * plan.waves;
     int64_t blocks = plan.work;
-    a.pace.unit_fp = 0;
-    a.pace.slots = nullptr;
-    a.pace.seq = 0;
+    pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
     if (plan.bpc > 0) {
         int occ = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, threads, 0) != hipSuccess || occ < 1) occ = 1;
         const int bpc = plan.bpc < occ ? plan.bpc : occ;
         const int64_t resident = (int64_t)plan.num_cus * bpc;
-        if (resident < blocks) blocks = resident;  // persistent: each workgroup strides over the work items
+        if (resident < blocks) {
+            // persistent: each workgroup strides over the work items.  A paced launch lasts as long as
+            // its busiest workgroup, so the items are dealt in whole rounds: with 25000 items and 1024
+            // resident workgroups, 1000 workgroups of 25 items each keep the whole launch busy to the end,
+            // where 1024 would leave 600 of them idle during the last of 25 rounds (2.4 % of the time).
+            const int64_t rounds = (plan.work + resident - 1) / resident;
+            const int64_t even = (plan.work + rounds - 1) / rounds;
+            blocks = (even * 8 >= resident * 7) ? even : resident;
+        }
         // Pacing needs every workgroup of the launch to be resident at once, which
         // holds here: blocks <= CUs x workgroups per CU that fit.
-        pace_setup(const_cast<gpga_ctx*>(plan.ctx), plan.pace_gbs, (double)blocks * plan.waves, plan.vec * 4, &a.pace);
+        pace_setup(const_cast<gpga_ctx*>(plan.ctx), plan.pace_gbs, plan.pace_key, (double)blocks * plan.waves, plan.vec * 4, &a.pace);
     }
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (plan.blocks_out) *plan.blocks_out = blocks;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(threads), 0, st, a);
     return hipGetLastError();
+}
+
+template <int MOM, int L>
+hipError_t launch_cycles_traced(bool traced, const LaunchPlan& plan, const CycleArgs& a, hipStream_t st) {
+    return traced ? launch_planned(k_step_cycles<MOM, L, true>, plan, a, st)
+                  : launch_planned(k_step_cycles<MOM, L, false>, plan, a, st);
+}
+template <int MOM>
+hipError_t launch_cycles_len(int L, bool traced, const LaunchPlan& plan, const CycleArgs& a, hipStream_t st) {
+    if (L == 2) return launch_cycles_traced<MOM, 2>(traced, plan, a, st);
+    if (L == 4) return launch_cycles_traced<MOM, 4>(traced, plan, a, st);
+    if (L == 8) return launch_cycles_traced<MOM, 8>(traced, plan, a, st);
+    return launch_cycles_traced<MOM, 16>(traced, plan, a, st);
+}
+hipError_t launch_cycles(int L, int mom, bool traced, const LaunchPlan& plan, const CycleArgs& a, hipStream_t st) {
+    if (mom == 2) return launch_cycles_len<2>(L, traced, plan, a, st);
+    return mom ? launch_cycles_len<1>(L, traced, plan, a, st) : launch_cycles_len<0>(L, traced, plan, a, st);
 }
 
 template <typename T, int MODE, int MOM>
@@ -777,16 +824,12 @@ hipError_t launch_global_u(int U, const LaunchPlan& plan, hipStream_t st, const 
 constexpr int64_t kPacedWaves = 2048;
 
 // Default policy: large launches whose wavefronts each walk many rows run
-// persistent and paced; everything else is a one-shot launch.
+// persistent and paced, at the rate the controller of their kind has found;
+// everything else is a one-shot launch.
 constexpr int kAutoBlocksPerCu = 4;
-constexpr double kAutoPaceGbsWalk = 6300.0;    // measured optimum of the gossip walk (cfg3 shape)
-constexpr double kAutoPaceGbsShort = 6150.0;   // walks over cycles of 8 rows
-constexpr double kAutoPaceGbsCycles = 6150.0;  // whole-cycle batches (cycles of 2 rows)
-constexpr double kAutoPaceGbsFour = 5950.0;    // walks over cycles of 4 rows
-constexpr double kAutoPaceGbsGlobal = 6300.0;  // same stream mix as the walk once the mean rows are deferred
 constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
-LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool walks_rows, double auto_gbs) {
+LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool walks_rows, int pace_key) {
     LaunchPlan p;
     p.work = work;
     p.num_cus = c->num_cus;
@@ -794,9 +837,10 @@ LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool w
     p.vec = vec;
     p.ctx = c;
     p.clock_hz = c->clock_hz;
+    p.pace_key = pace_key;
     const bool big = walks_rows && vec == 4 && (int64_t)c->n * c->d * 4 >= kPaceMinBytes;
     p.bpc = c->opt_blocks_per_cu < 0 ? (big ? kAutoBlocksPerCu : 0) : c->opt_blocks_per_cu;
-    p.pace_gbs = c->opt_pace_gbs < 0 ? (big ? auto_gbs : 0.0) : (double)c->opt_pace_gbs;
+    p.pace_gbs = c->opt_pace_gbs < 0 ? (big ? -1.0 : 0.0) : (double)c->opt_pace_gbs;
     if (!walks_rows) p.pace_gbs = 0.0;
     return p;
 }
@@ -822,30 +866,26 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     const int waves = c->opt_waves ? c->opt_waves : 4;
     const int64_t tiles = (ge.ncols + kWave - 1) / kWave;
 
-    // One-peer offset n/2 on large problems (cycles of two rows): whole-cycle batches, persistent and
-    // paced.  Measured on the n = 64, d = 25.6M shape: 6.00 TB/s at a 6.15 TB/s target against 5.80
-    // for the one-shot walk.  (Cycles of four rows run a little faster as a paced walk, below.)
-    if (mode == MODE_PEER && vec == 4 && a.L == 2 && !c->opt_row_split && c->opt_cycle_kernel != 0 &&
-        (tiles >= kPacedWaves || c->opt_cycle_kernel == 1)) {
+    // One-peer steps over short cycles (2, 4, 8 or 16 rows) on large problems: the row-streaming kernel,
+    // persistent and paced.
+    if (mode == MODE_PEER && vec == 4 && (a.L == 2 || a.L == 4 || a.L == 8 || a.L == 16) && !c->opt_row_split &&
+        c->opt_cycle_kernel != 0 && (tiles >= kPacedWaves || c->opt_cycle_kernel == 1)) {
         CycleArgs ca;
         ca.ge = ge;
         ca.S = S;
         ca.C = a.C;
         ca.gx = (tiles + waves - 1) / waves;
-        LaunchPlan plan = make_plan(c, ca.gx, waves, vec, true, kAutoPaceGbsCycles);
+        LaunchPlan plan = make_plan(c, ca.gx, waves, vec, true,
+                                    a.L == 2 ? PACE_CYCLES : a.L == 4 ? PACE_PEER_4 : a.L == 8 ? PACE_PEER_8 : PACE_PEER_16);
         if (c->opt_blocks_per_cu < 0 && plan.bpc == 0) plan.bpc = kAutoBlocksPerCu;  // forced on a small problem
         const int momk = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
         ca.spread_partials = nullptr;
-        if (spread_partials && spread_count) {  // every lane stores whole columns: the consensus sums ride along
+        const bool traced = spread_partials && spread_count;  // every lane stores whole columns: the consensus sums ride along
+        if (traced) {
             ca.spread_partials = spread_partials;
             plan.blocks_out = spread_count;
-            if (momk == 2) return launch_planned(k_step_cycles<2, 2, true>, plan, ca, c->stream);
-            return momk ? launch_planned(k_step_cycles<1, 2, true>, plan, ca, c->stream)
-                        : launch_planned(k_step_cycles<0, 2, true>, plan, ca, c->stream);
         }
-        if (momk == 2) return launch_planned(k_step_cycles<2, 2>, plan, ca, c->stream);
-        return momk ? launch_planned(k_step_cycles<1, 2>, plan, ca, c->stream)
-                    : launch_planned(k_step_cycles<0, 2>, plan, ca, c->stream);
+        return launch_cycles(a.L, momk, traced, plan, ca, c->stream);
     }
 
     int Q = 1;
@@ -881,12 +921,14 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     // cycles of 4 rows and more are paced (a work item then takes all cycles of its tile, below);
     // shorter ones keep few rows open in a one-shot launch anyway
     const int min_cycle = c->opt_pace_min_cycle > 0 ? c->opt_pace_min_cycle : 4;
-    // short cycles peak at lower targets than long walks (n = 64, d = 25.6M): 8 rows 5.97 TB/s at
-    // 6.15-6.2 (5.81 at 6.3); 4 rows 5.78 TB/s at 5.9-6.0 (5.63 at 6.1)
-    const double auto_gbs = a.L <= 4 ? kAutoPaceGbsFour : a.L <= 8 ? kAutoPaceGbsShort : kAutoPaceGbsWalk;
-    const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= min_cycle, auto_gbs);
+    // short cycles sustain lower rates than long walks (measured on n = 64, d = 25.6M: 8 rows 5.97 TB/s,
+    // 4 rows 5.78 TB/s, long walks 6.15 TB/s), so each class has a controller of its own
+    const int pace_key = mode == MODE_RING ? PACE_RING
+                         : mode != MODE_PEER ? PACE_SELF
+                         : a.L <= 4 ? PACE_PEER_4 : a.L <= 8 ? PACE_PEER_8 : PACE_PEER_LONG;
+    const LaunchPlan plan = make_plan(c, gx * gy, waves, vec, uniform && a.L >= min_cycle, pace_key);
     // paced wavefronts advance one row per batch (two rows in flight); free-running ones two
-    const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : kDefaultUnroll);
+    const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs != 0.0 ? 1 : kDefaultUnroll);
     const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     a.spread_partials = nullptr;
     a.cpi = 1;
@@ -894,7 +936,7 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
     // Paced launches with one cycle per workgroup: a work item takes ALL cycles of its column tile
     // in turn instead of one (measured 3.41 -> 3.33 ms on n = 1024, d = 1M); its lanes then store
     // whole columns, as they do when there is a single cycle.
-    if (a.C > 1 && Q == 1 && wpb == 1 && plan.pace_gbs > 0.0 && plan.bpc > 0 && mode == MODE_PEER) {
+    if (a.C > 1 && Q == 1 && wpb == 1 && plan.pace_gbs != 0.0 && plan.bpc > 0 && mode == MODE_PEER) {
         a.cpi = a.C;
         a.gy = 1;
         lp.work = a.gx;
@@ -950,8 +992,8 @@ hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     if (gx > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     a.gx = gx;
     a.xcd = c->opt_xcd_swizzle;
-    const LaunchPlan plan = make_plan(c, gx, waves, vec, RL == 1 && wpb == 1 && n >= 8, kAutoPaceGbsGlobal);
-    const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs > 0.0 ? 1 : 4);
+    const LaunchPlan plan = make_plan(c, gx, waves, vec, RL == 1 && wpb == 1 && n >= 8, PACE_GLOBAL);
+    const int U = c->opt_unroll ? c->opt_unroll : (plan.pace_gbs != 0.0 ? 1 : 4);
     const int mom = c->mu != 0.f ? (c->nesterov ? 2 : 1) : 0;
     if (vec == 4) {
         if (mom == 2) return launch_global_u<v4f, 2>(U, plan, c->stream, a);

@@ -172,6 +172,13 @@ class Simulation:
         B.gpga_mean(self.ctx, out)
         return out
 
+    def tune(self, launches: int = 16):
+        """Let the pacing controllers settle (state arrays are left with unspecified contents)."""
+        B.gpga_tune(self.ctx, launches)
+
+    def query(self, name: str) -> float:
+        return B.gpga_query(self.ctx, name)
+
     def set_option(self, name: str, value: int):
         B.gpga_set_option(self.ctx, name, value)
 

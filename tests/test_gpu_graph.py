@@ -63,3 +63,57 @@ def test_captured_trajectory_replays_to_the_eager_result(hx, n, d, topology, opt
             assert torch.equal(sim.M, M_eager), rep
             assert torch.equal(trace, tr_eager), rep
     sim.close()
+
+
+def test_paced_launches_stay_paced_when_a_captured_graph_replays(hx):
+    # The pacing state lives on the device and resets itself at the end of every launch, so a
+    # replayed launch publishes a fresh start time like an eager one.  Evidence that does not
+    # depend on timing: every replayed launch is counted by its controller, and the slowest
+    # wavefront of the last one ended within a fraction of a millisecond of its last deadline
+    # (against a stale start time it would be late by the whole time since capture).
+    # The event times of replay and eager run are compared as well.
+    c = inputs.CONFIGS["cfg3"]
+    n, d, T = c["n"], c["d"], 20
+    stream = torch.cuda.Stream()
+    sim = hx.Simulation(n, d, topology="expo1", H=c["H"], lr=c["lr"], momentum=c["momentum"], stream=stream)
+    sim.problem_synthetic(c["seed"], c["grad_var"])
+    kinds = ("peer_long", "peer_16", "peer_8", "peer_4", "cycles")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    with torch.cuda.stream(stream):
+        sim.tune(16)
+        sim.set_state(k=0)
+        sim.run(T)                                    # warm
+        sim.set_state(k=0)
+        ev[0].record()
+        sim.run(T)
+        ev[1].record()
+        torch.cuda.synchronize()
+        X_eager = sim.X.clone()                       # two eager runs: x / x_new are back in their roles
+        eager_ms = ev[0].elapsed_time(ev[1])
+        count = lambda k: sim.query(f"pace_launches:{k}") + sim.query(f"pace_launches:{k}/1")   # both directions
+        before = {k: count(k) for k in kinds}
+        sim.set_state(k=0)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            sim.run(T)
+        torch.cuda.synchronize()
+        captured = {k: count(k) for k in kinds}
+        assert captured == before                     # capture itself runs nothing
+        graph.replay()                                # warm
+        ev[2].record()
+        graph.replay()
+        ev[3].record()
+        torch.cuda.synchronize()
+        replay_ms = ev[2].elapsed_time(ev[3])
+    after = {k: count(k) for k in kinds}
+    per_kind = dict.fromkeys(kinds, 0)
+    for k in range(T):                                # offsets 1, 2 | 4 | 8 | 16 | 32 on n = 64
+        per_kind[("peer_long", "peer_long", "peer_16", "peer_8", "peer_4", "cycles")[k % 6]] += 1
+    for kind in kinds:
+        assert after[kind] - captured[kind] == 2 * per_kind[kind], (kind, captured, after)
+        for d in ("", "/1"):
+            late, plan = sim.query(f"pace_last_late_us:{kind}{d}"), sim.query(f"pace_last_plan_us:{kind}{d}")
+            assert plan > 1000.0 and late < 0.1 * plan, f"{kind}{d}: ended {late:.0f} us after its last deadline (plan {plan:.0f} us)"
+    print(f"cfg3-shaped {T}-step trajectory: eager {eager_ms:.2f} ms, graph replay {replay_ms:.2f} ms")
+    assert replay_ms <= 1.03 * eager_ms
+    sim.close()
