@@ -189,9 +189,9 @@ gpga_status gpga_step(gpga_ctx* ctx);
  * of the same loop unless option "small_run" is 0: whole iterations - gradients,
  * momentum and local update, gossip step or global average, consensus trace - run
  * inside single-workgroup launches of up to 256 iterations with the state in LDS.
- * The results are the same to rounding; x is then updated IN PLACE (x / x_new are
- * not swapped: gpga_current_x tells), m as usual, and g holds the gradients of the
- * last iteration. */
+ * The results are the same to rounding and land where T separate steps leave them:
+ * the live X (gpga_current_x) in the same one of the two bound arrays, m updated,
+ * g holding the gradients of the last iteration. */
 gpga_status gpga_run(gpga_ctx* ctx, int64_t T, const int32_t* batch_table_dev, int32_t B);
 
 /* Attach an arbitrary weight matrix W (Sec. 3: W >= 0, W 1 = 1, 1^T W = 1^T,
@@ -202,9 +202,10 @@ gpga_status gpga_run(gpga_ctx* ctx, int64_t T, const int32_t* batch_table_dev, i
  * EINVAL if an index is out of range, a weight is negative or not finite, or a
  * row or column sum differs from 1 by more than 1e-5.  Synchronises the stream.
  * Gossip steps with GRID, EXPO and CUSTOM run as one fused kernel (the column
- * tile of all n rows staged in LDS, 20 B per element) for n <= 256; above that
- * they run as a local-update pass that OVERWRITES g_dev with x^(k+1/2), followed
- * by a sparse product. */
+ * tile of all n rows staged in LDS, 20 B per element) while the tile fits in LDS;
+ * above that they run as a local-update pass followed by a sparse product.  On
+ * every path g_dev is only read, and the array that held X^(k) holds unspecified
+ * values after the step (as after any step: it is the target of the next one). */
 gpga_status gpga_set_mixing_csr(gpga_ctx* ctx, const int64_t* row_ptr_host, const int32_t* col_host,
                                 const float* val_host);
 
@@ -264,6 +265,12 @@ gpga_status gpga_set_trace(gpga_ctx* ctx, double* trace_dev, int64_t capacity);
 /* xbar = (1/n) sum_i x_i (App. A notation) of the live X into xbar_dev (d floats
  * on the device, caller-owned). */
 gpga_status gpga_mean(gpga_ctx* ctx, float* xbar_dev);
+
+/* Node average of one scalar per node: out_dev[0] = (1/n) sum_i v_dev[i] (n floats in, one
+ * double out, both on the DEVICE; fp64 accumulation in a fixed order).  With the losses of
+ * gpga_local_loss it is the F of Algorithm 2, and at a common point xbar the global
+ * objective f(xbar) = (1/n) sum_i f_i(xbar) of eq. (1).  Asynchronous on the bound stream. */
+gpga_status gpga_node_mean(gpga_ctx* ctx, const float* v_dev, double* out_dev);
 
 /* Device pointer of the live X (x_dev or x_new_dev of gpga_bind). */
 gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);

@@ -63,6 +63,7 @@ SIGNATURES = [
     ("gpga_consensus_error_static", _c.c_int, [_ctx_p, _c.c_void_p]),
     ("gpga_set_trace", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_int64]),
     ("gpga_mean", _c.c_int, [_ctx_p, _c.c_void_p]),
+    ("gpga_node_mean", _c.c_int, [_ctx_p, _c.c_void_p, _c.c_void_p]),
     ("gpga_current_x", _c.c_int, [_ctx_p, _c.POINTER(_c.c_void_p)]),
     ("gpga_set_option", _c.c_int, [_ctx_p, _c.c_char_p, _c.c_int64]),
     ("gpga_tune", _c.c_int, [_ctx_p, _c.c_int32]),
@@ -278,6 +279,11 @@ def gpga_set_trace(ctx, trace, capacity: int = 0):
 
 def gpga_mean(ctx, xbar):
     _check(ctx, _lib.gpga_mean(ctx, _ptr(xbar)))
+
+
+def gpga_node_mean(ctx, v, out):
+    """v: n floats on the device; out: one float64 on the device."""
+    _check(ctx, _lib.gpga_node_mean(ctx, _ptr(v), _ptr(out)))
 
 
 def gpga_current_x(ctx) -> int:

@@ -681,6 +681,11 @@ gpga_status gpga_run(gpga_ctx* c, int64_t T, const int32_t* batch_table_dev, int
             for (int32_t t = 0; t < chunk; ++t) lr[t] = scheduled_lr(c, c->k + t);
             const hipError_t e = launch_small_run(c, chunk, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, lr);
             if (e != hipSuccess) return hip_fail(c, e, "small-problem kernel launch");
+            if (chunk % 2) {  // the launch left X where `chunk` separate steps would have: swap the roles like they do
+                float* t = c->x;
+                c->x = c->x_new;
+                c->x_new = t;
+            }
             c->k += chunk;
             j += chunk;
         }
@@ -770,6 +775,17 @@ gpga_status gpga_mean(gpga_ctx* c, float* xbar_dev) {
     DeviceGuard guard(c->device);
     hipError_t e = launch_col_mean(c, xbar_dev);
     if (e != hipSuccess) return hip_fail(c, e, "mean kernel launch");
+    return GPGA_OK;
+}
+
+gpga_status gpga_node_mean(gpga_ctx* c, const float* v_dev, double* out_dev) {
+    if (!c) return GPGA_EINVAL;
+    if (!v_dev || !aligned(v_dev, 4)) return fail(c, GPGA_EINVAL, "v_dev must be a 4-byte aligned device pointer");
+    if (!out_dev || !aligned(out_dev, 8)) return fail(c, GPGA_EINVAL, "out_dev must be an 8-byte aligned device pointer");
+    if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
+    DeviceGuard guard(c->device);
+    const hipError_t e = launch_mean_f32(c, v_dev, c->n, out_dev);
+    if (e != hipSuccess) return hip_fail(c, e, "node mean launch");
     return GPGA_OK;
 }
 

@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(256) k_rows_accum(const float* __restrict__ fe
         out.y = (float)a1;
         out.z = (float)a2;
         out.w = (float)a3;
-        reinterpret_cast<v4f*>(gi)[t] = out;
+        __builtin_nontemporal_store(out, reinterpret_cast<v4f*>(gi) + t);
     } else {
         if (t >= d) return;
         double a0 = 0;
@@ -409,7 +409,9 @@ __global__ void __launch_bounds__(256) k_virtual_accum(const float* __restrict__
         out.y = (float)a1;
         out.z = (float)a2;
         out.w = (float)a3;
-        *reinterpret_cast<v4f*>(row + c) = out;
+        // streamed past the caches: the fused step that follows reads g once, and dirty lines left behind
+        // here would be written back while that step is already being timed against its pacing clock
+        __builtin_nontemporal_store(out, reinterpret_cast<v4f*>(row + c));
     } else {
         row[c] = (float)a0;
         if (c + 1 < d) row[c + 1] = (float)a1;
@@ -434,7 +436,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // state and x^(k+1/2) are fp32, the mean of a global average is one value broadcast to
 // all rows.
 struct SmallArgs {
-    float* x;  // n x ld, updated in place
+    const float* x;  // n x ld, the iterates before the first iteration of this launch
+    float* x_out;    // n x ld, receives the iterates after the last one (may be the same array)
     float* m;  // n x ld momentum buffers (unused when mu = 0)
     float* g;  // n x ld, receives the gradients of the last iteration
     int64_t ld;
@@ -694,7 +697,7 @@ __global__ void __launch_bounds__(kSmallRunThreads) k_small_run(const SmallArgs 
 
     for (int e = tid; e < nd; e += blockDim.x) {
         const int i = e / d, c = e - i * d;
-        a.x[(int64_t)i * a.ld + c] = sX[e];
+        a.x_out[(int64_t)i * a.ld + c] = sX[e];
         if (MOM) a.m[(int64_t)i * a.ld + c] = sM[e];
     }
 }
@@ -828,6 +831,7 @@ hipError_t launch_small_run(const gpga_ctx* c, int32_t T, const int32_t* idx, in
     if (T < 1 || T > kSmallRunMaxIters) return hipErrorInvalidValue;
     SmallArgs a;
     a.x = c->x;
+    a.x_out = (T % 2) ? c->x_new : c->x;  // where T separate steps would leave the live iterates
     a.m = c->m;
     a.g = c->g;
     a.ld = c->ld;

@@ -22,7 +22,7 @@ enum StencilMode : int {
     MODE_RING = 0,  // (prev + cur + next) / 3
     MODE_PEER = 1,  // (cur + next) / 2
     MODE_SELF = 2,  // cur
-    MODE_INPLACE = 3  // cur, stored over the gradient it was computed from (x_new untouched)
+    MODE_INPLACE = 3  // cur, stored over the old iterate it was computed from (x_new and g untouched)
 };
 
 // A sparse mixing matrix W in compressed-row form: row i lists the nodes j whose
@@ -175,8 +175,9 @@ hipError_t launch_synth_grad(const gpga_ctx* c);
 hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
 hipError_t launch_virtual_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, float* loss_out);
 // Small problems: T <= kSmallRunMaxIters whole iterations (stored-feature gradients, update,
-// mix or average, consensus trace) in one single-workgroup launch, x updated in place and
-// g left holding the last gradients; lr[t] is the step size of iteration c->k + t.
+// mix or average, consensus trace) in one single-workgroup launch; the final iterates go to the
+// array T separate steps would leave them in (c->x for even T, c->x_new for odd T: the caller
+// swaps the roles), g is left holding the last gradients; lr[t] is the step size of iteration c->k + t.
 // small_run_fits tells whether the context's problem and sizes qualify.
 bool small_run_fits(const gpga_ctx* c, const int32_t* idx, int32_t B);
 hipError_t launch_small_run(const gpga_ctx* c, int32_t T, const int32_t* idx, int32_t B, const float* lr);

@@ -14,8 +14,8 @@
 //    element of x, m, g is read from HBM once and m, x_new written once (20 B per
 //    element), exactly like the ring / one-peer stencil kernels.
 //  * two-pass path (more rows than LDS can hold): pass 1 is the elementwise local
-//    update (the W = I walk of the stencil kernel), which overwrites g with y
-//    (g is consumed by the step anyway);
+//    update (the W = I walk of the stencil kernel), which writes y over the old
+//    iterate x (dead once y exists: that array is the target of the next step);
 //    pass 2 is the sparse product x_new = W y with workgroups ordered so that
 //    all rows of a column tile run together and re-reads of y hit the caches
 //    (28 B per element of HBM traffic when they do).
@@ -365,12 +365,12 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
 
 template <typename T>
 hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int vec) {
-    // pass 1: the W = I walk of the stencil kernel, storing y = x^(k+1/2) over g
+    // pass 1: the W = I walk of the stencil kernel, storing y = x^(k+1/2) over the old iterate
     hipError_t e = launch_step_walk(c, ge, MODE_INPLACE, 0, vec);
     if (e != hipSuccess) return e;
     const int64_t tiles = (ge.ncols + 255) / 256;
     if (tiles * ge.n > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((k_spmm_rows<T>), dim3((unsigned)(tiles * ge.n)), dim3(256), 0, c->stream, ge.g, ge.x_new,
+    hipLaunchKernelGGL((k_spmm_rows<T>), dim3((unsigned)(tiles * ge.n)), dim3(256), 0, c->stream, ge.x, ge.x_new,
                        ge.ld, ge.col0, ge.ncols, ge.n, tiles, w);
     return hipGetLastError();
 }

@@ -16,8 +16,8 @@
 // permutation i -> (i + S) mod n:
 //   ring      S = 1      one cycle of length n, taps (prev, cur, next)/3
 //   one-peer  S = 2^s    gcd(S,n) cycles of length n/gcd, taps (cur, next)/2
-//   W = I     -          n cycles of length 1, tap cur (also used, writing y over g,
-//                        as the first pass of sparse-W steps with many rows)
+//   W = I     -          n cycles of length 1, tap cur (also used, writing y over the old
+//                        iterate, as the first pass of sparse-W steps with many rows)
 // A "walker" is one wavefront walking a contiguous segment of one cycle with
 // the last two y values kept in registers.  When a cycle is split over Q
 // wavefronts of a workgroup (few columns, many rows) the first/last y of every
@@ -242,15 +242,15 @@ __global__ void __launch_bounds__(kWave* kMaxWaves) k_step_walk(const WalkArgs a
                 if (TRACE && cc == 0) spread.reset(x0);
                 yf = y_of(x0, m0, g0, r0);
                 if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r0 * ldT, yf);
-                // in place: through a pointer derived from gp, the one this element was read with
-                if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(gp) + (int64_t)r0 * ldT, yf);
+                // in place: over the old iterate, through a pointer derived from the one it was read with
+                if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(xp) + (int64_t)r0 * ldT, yf);
                 pc = yf;
                 row_prev = r0;
                 if (len >= 2) {
                     ys = y_of(x1, m1, g1, r1);
                     if (MODE == MODE_PEER) put(r0, (yf + ys) * 0.5f);
                     if (MODE == MODE_SELF) st_stream(xnp + (int64_t)r1 * ldT, ys);
-                    if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(gp) + (int64_t)r1 * ldT, ys);
+                    if (MODE == MODE_INPLACE) st_stream(const_cast<T*>(xp) + (int64_t)r1 * ldT, ys);
                     pp = yf;
                     pc = ys;
                     row_prev = r1;

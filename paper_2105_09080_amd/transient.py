@@ -43,18 +43,20 @@ class LossProbe:
         B.gpga_problem_logreg(self.sim.ctx, feat_dev, y_dev, M)
         with torch.cuda.stream(stream):
             self.xbar = torch.empty(d, dtype=torch.float32, device=self.sim.device)
-            self.losses = torch.empty((capacity, n), dtype=torch.float32, device=self.sim.device)
+            self.losses = torch.empty(n, dtype=torch.float32, device=self.sim.device)
+            self.means = torch.empty(capacity, dtype=torch.float64, device=self.sim.device)
         self.count = 0
 
     def __call__(self, run: Simulation):
         B.gpga_mean(run.ctx, self.xbar)
         B.gpga_reset(self.sim.ctx, self.xbar)
-        B.gpga_local_loss(self.sim.ctx, None, 0, self.losses[self.count])
+        B.gpga_local_loss(self.sim.ctx, None, 0, self.losses)
+        B.gpga_node_mean(self.sim.ctx, self.losses, self.means[self.count:])   # f(xbar) = (1/n) sum_i f_i(xbar)
         self.count += 1
 
     def values(self) -> np.ndarray:
         self.sim.stream.synchronize()        # the kernels ran on the simulation's stream, not torch's current one
-        return self.losses[: self.count].cpu().numpy().astype(np.float64).mean(axis=1)
+        return self.means[: self.count].cpu().numpy()
 
     def close(self):
         self.sim.close()

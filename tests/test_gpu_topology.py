@@ -101,7 +101,7 @@ def test_sparse_W_step_matches_oracle(hx, n, d, pad, topology, momentum, nestero
 
 
 @pytest.mark.parametrize("n,d,topology", [(20, 1031, "grid"), (64, 4100, "expo"), (100, 515, "grid")])
-def test_two_pass_path_gives_the_tile_kernels_answer_and_leaves_y_in_g(hx, n, d, topology):
+def test_two_pass_path_gives_the_tile_kernels_answer_and_leaves_g_alone(hx, n, d, topology):
     X, Mb, G = inputs.random_state(n, d, seed=31 + n)
     outs = []
     for two_pass in (0, 1):
@@ -112,12 +112,10 @@ def test_two_pass_path_gives_the_tile_kernels_answer_and_leaves_y_in_g(hx, n, d,
         outs.append((host(sim.X), host(sim.M), host(sim.G)))
         sim.close()
     X_ref, M_ref = orc.gossip_pga_step(X, Mb, G, 0, topology=topology, H=0, lr=0.1, momentum=0.9)
-    Y_ref, _ = orc.local_update(X, Mb, G, 0.1, 0.9)
-    for Xg, Mg, _ in outs:
+    for Xg, Mg, Gg in outs:
         assert_close(Xg, X_ref, TOL_STEP, "X")
         assert_close(Mg, M_ref, TOL_STEP, "M")
-    np.testing.assert_array_equal(outs[0][2], G)          # fused tile kernel: g untouched
-    assert_close(outs[1][2], Y_ref, TOL_STEP, "g after the two-pass step holds x^(k+1/2)")
+        np.testing.assert_array_equal(Gg, G)             # both paths leave the gradients as they were
 
 
 @pytest.mark.parametrize("opts", [{"blocks_per_cu": 1}, {"blocks_per_cu": 1, "pace_gbs": 3000},
