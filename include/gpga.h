@@ -211,7 +211,9 @@ gpga_status gpga_set_mixing_csr(gpga_ctx* ctx, const int64_t* row_ptr_host, cons
 
 /* Connectivity beta = ||W - (1/n) 1 1^T||_2 (Assumption 3) of the context's
  * current W (for the one-peer graph: the matrix of the current iteration),
- * computed on the host by Lanczos iteration in double precision. */
+ * computed on the host by Lanczos iteration in double precision (a Krylov space of at
+ * most 1024 vectors and 256 MiB: exact to ~1e-7 for n up to a few thousand; for much
+ * larger n with a tiny spectral gap the value is a lower bound of beta). */
 gpga_status gpga_mixing_beta(gpga_ctx* ctx, double* beta_out);
 /* The same for a named graph (not CUSTOM) without a context or a device. */
 gpga_status gpga_topology_beta(int32_t topology, int32_t n, int64_t k, double* beta_out);

@@ -61,5 +61,22 @@ def build_library(verbose: bool = True) -> str:
     return LIB_PATH
 
 
+HOST_CHECK_PATH = os.path.join(OBJ_DIR, "gpga_host_check")
+
+
+def build_host_check(verbose: bool = True) -> str:
+    """The host-only check program (graph builders, validation of W, beta, schedule arithmetic) compiled from
+    the library's own sources with AddressSanitizer and UndefinedBehaviorSanitizer on the host side.  Runs on
+    the CPU; returns the path of the executable."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    cmd = [hipcc_path(), "-x", "hip", "--cuda-host-only", "-std=c++17", "-O1", "-g",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           os.path.join(CSRC, "gpga_graph.hip"), os.path.join(CSRC, "gpga_host_check.cpp"), "-o", HOST_CHECK_PATH]
+    _run(cmd, verbose)
+    return HOST_CHECK_PATH
+
+
 if __name__ == "__main__":
     print(build_library())

@@ -10,6 +10,7 @@
 
 #include "gpga_internal.hpp"
 #include "gpga_pace.hpp"
+#include "gpga_schedule.hpp"
 
 namespace {
 
@@ -50,12 +51,6 @@ struct DeviceGuard {
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-int tau_of(int32_t n) {  // number of offsets of the one-peer exponential graph
-    int t = 0;
-    while ((1LL << t) < n) ++t;
-    return t < 1 ? 1 : t;
-}
-
 bool is_pow2_le8(int64_t v) { return v == 1 || v == 2 || v == 4 || v == 8; }
 
 gpga_status grow_f32(gpga_ctx* c, float** p, size_t* cap, size_t need) {
@@ -82,38 +77,6 @@ gpga_status grow_f64(gpga_ctx* c, double** p, size_t* cap, size_t need) {
     if (e != hipSuccess) return hip_fail(c, e, "hipMalloc(scratch)");
     *cap = need;
     return GPGA_OK;
-}
-
-// gamma_k of the attached schedule for iteration k.
-float scheduled_lr(const gpga_ctx* c, int64_t k) {
-    double lr = c->lr;
-    switch (c->sched) {
-        case SCHED_STEP:
-            lr = c->sched_base * std::pow(c->sched_factor, (double)(k / c->sched_period));
-            break;
-        case SCHED_MILESTONES:
-            if (k < c->sched_warmup) {
-                lr = c->sched_start + (c->sched_base - c->sched_start) * ((double)k / (double)c->sched_warmup);
-            } else {
-                int passed = 0;
-                for (int j = 0; j < c->sched_count; ++j) passed += (k >= c->sched_milestones[j]);
-                lr = c->sched_base * std::pow(c->sched_factor, (double)passed);
-            }
-            break;
-        case SCHED_POLY:
-            if (k < c->sched_warmup) {
-                lr = c->sched_base * ((double)k / (double)c->sched_warmup);
-            } else if (k >= c->sched_total) {
-                lr = 0.0;
-            } else {
-                const double left = 1.0 - (double)(k - c->sched_warmup) / (double)(c->sched_total - c->sched_warmup);
-                lr = c->sched_base * std::pow(left, c->sched_power);
-            }
-            break;
-        default:
-            break;
-    }
-    return (float)lr;
 }
 
 bool finite_nonneg(float v) { return std::isfinite(v) && v >= 0.f; }
@@ -158,27 +121,12 @@ gpga_status upload_csr(gpga_ctx* c) {
 bool named_graph_csr(int32_t topo, int32_t n, int64_t k, HostCsr* out) {
     switch (topo) {
         case GPGA_TOPO_RING: build_ring_csr(n, out); return true;
-        case GPGA_TOPO_EXPO1: build_one_peer_csr(n, (int32_t)((1LL << (k % tau_of(n))) % n), out); return true;
+        case GPGA_TOPO_EXPO1: build_one_peer_csr(n, one_peer_shift(n, k), out); return true;
         case GPGA_TOPO_NONE: build_one_peer_csr(n, 0, out); return true;  // 1/2 + 1/2 on the diagonal
         case GPGA_TOPO_GRID: build_grid_csr(n, out); return true;
         case GPGA_TOPO_EXPO: build_static_expo_csr(n, out); return true;
         default: return false;
     }
-}
-
-// Copies a caller's CSR arrays after range checks on the row pointers.
-const char* copy_csr(int32_t n, const int64_t* row_ptr, const int32_t* col, const float* val, HostCsr* out) {
-    if (!row_ptr || row_ptr[0] != 0) return "row_ptr must start at 0";
-    for (int32_t i = 0; i < n; ++i)
-        if (row_ptr[i + 1] < row_ptr[i]) return "row_ptr must be non-decreasing";
-    const int64_t nnz = row_ptr[n];
-    if (nnz < n || nnz > 0x7fffffffLL) return "W needs between n and 2^31-1 entries";
-    if (!col || !val) return "col and val must not be NULL";
-    out->ptr.resize((size_t)n + 1);
-    for (int32_t i = 0; i <= n; ++i) out->ptr[i] = (int32_t)row_ptr[i];
-    out->col.assign(col, col + nnz);
-    out->val.assign(val, val + nnz);
-    return nullptr;
 }
 
 constexpr double kStochasticTol = 1e-5;  // |row / column sum - 1| allowed for fp32 weights
@@ -509,7 +457,7 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
             mode = MODE_RING;
             S = 1;
         } else if (c->topo == GPGA_TOPO_EXPO1) {
-            S = (int32_t)((1LL << (c->k % tau_of(c->n))) % c->n);
+            S = one_peer_shift(c->n, c->k);
             mode = S ? MODE_PEER : MODE_SELF;
         }
     }
@@ -586,8 +534,7 @@ gpga_status gpga_step(gpga_ctx* c) {
     if (!c->bound) return fail(c, GPGA_ESTATE, "buffers are not bound (gpga_bind)");
     if (c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is enabled: call gpga_aga_step");
     DeviceGuard guard(c->device);
-    const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
-    return run_step(c, global);
+    return run_step(c, is_global_iteration(c->topo, c->H, c->k));
 }
 
 gpga_status gpga_set_mixing_csr(gpga_ctx* c, const int64_t* row_ptr_host, const int32_t* col_host,
@@ -694,8 +641,7 @@ gpga_status gpga_run(gpga_ctx* c, int64_t T, const int32_t* batch_table_dev, int
     for (int64_t j = 0; j < T; ++j) {
         gpga_status s = run_grad(c, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, nullptr);
         if (s != GPGA_OK) return s;
-        const bool global = (c->topo == GPGA_TOPO_FULL) || (c->H > 0 && (c->k + 1) % c->H == 0);
-        s = run_step(c, global);
+        s = run_step(c, is_global_iteration(c->topo, c->H, c->k));
         if (s != GPGA_OK) return s;
     }
     return GPGA_OK;

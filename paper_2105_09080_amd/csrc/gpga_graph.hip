@@ -10,6 +10,7 @@
 #include <map>
 
 #include "gpga_internal.hpp"
+#include "gpga_schedule.hpp"
 
 namespace {
 
@@ -26,12 +27,6 @@ void from_rows(const std::vector<std::map<int32_t, double>>& rows, HostCsr* out)
         }
         out->ptr.push_back((int32_t)out->col.size());
     }
-}
-
-int tau_of(int32_t n) {
-    int t = 0;
-    while ((1LL << t) < n) ++t;
-    return t < 1 ? 1 : t;
 }
 
 // y = W v  /  y = W^T v  in double.
@@ -206,4 +201,18 @@ double mixing_beta(int32_t n, const HostCsr& w) {
         for (int32_t i = 0; i < n; ++i) v[i] = z[i] / b;
     }
     return std::sqrt(std::max(best, 0.0));
+}
+
+const char* copy_csr(int32_t n, const int64_t* row_ptr, const int32_t* col, const float* val, HostCsr* out) {
+    if (!row_ptr || row_ptr[0] != 0) return "row_ptr must start at 0";
+    for (int32_t i = 0; i < n; ++i)
+        if (row_ptr[i + 1] < row_ptr[i]) return "row_ptr must be non-decreasing";
+    const int64_t nnz = row_ptr[n];
+    if (nnz < n || nnz > 0x7fffffffLL) return "W needs between n and 2^31-1 entries";
+    if (!col || !val) return "col and val must not be NULL";
+    out->ptr.resize((size_t)n + 1);
+    for (int32_t i = 0; i <= n; ++i) out->ptr[i] = (int32_t)row_ptr[i];
+    out->col.assign(col, col + nnz);
+    out->val.assign(val, val + nnz);
+    return nullptr;
 }

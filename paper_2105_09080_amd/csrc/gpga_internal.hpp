@@ -163,6 +163,8 @@ void build_ring_csr(int32_t n, HostCsr* out);
 void build_one_peer_csr(int32_t n, int32_t shift, HostCsr* out);
 void build_grid_csr(int32_t n, HostCsr* out);
 void build_static_expo_csr(int32_t n, HostCsr* out);
+// Copies a caller's CSR arrays after range checks on the row pointers; nullptr, or what is wrong.
+const char* copy_csr(int32_t n, const int64_t* row_ptr, const int32_t* col, const float* val, HostCsr* out);
 // Checks shape, index range, non-negativity and row / column sums (|sum - 1| <= tol).
 // Returns nullptr when W is acceptable, else a static description of the defect.
 const char* validate_csr(int32_t n, const HostCsr& w, double tol);
