@@ -343,8 +343,11 @@ __global__ void __launch_bounds__(256) k_virtual_margin(const float* __restrict_
         for (int b = 0; b < BMAX; ++b) {
             if (b < B) {
                 const v4f h = virtual_quad(mu, (uint32_t)q, i, (uint32_t)idx[(int64_t)i * B + b], k0, k1);
-                acc[b] += (double)h.x * xv.x + (double)h.y * xv.y + (double)h.z * xv.z +
-                          (double)h.w * xv.w;
+                // the four products of a quad are summed in fp32 (three roundings of ~6e-8 relative to
+                // the quad's own terms, random in sign over the d/4 quads of a margin), the quads in fp64:
+                // 6 issue slots per sample where four conversions and four fp64 operations took 12
+                const float t = h.x * xv.x + h.y * xv.y + h.z * xv.z + h.w * xv.w;
+                acc[b] += (double)t;
             }
         }
     }
@@ -390,18 +393,25 @@ __global__ void __launch_bounds__(256) k_virtual_accum(const float* __restrict__
     const int64_t c = q * 4;
     if (c >= d) return;
     const v4f mu = mu_sigma * normals4((uint32_t)q, i, 0u, TAG_MU, k0, k1);
-    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    // g = sum_b coef_b h_b over at most 32 samples of similar size: fp32 fused multiply-adds (error
+    // <= 32 x 6e-8 of sum |coef_b h_b|, far inside 1e-5 of the row's scale).  A sample whose
+    // coefficient is exactly zero adds exactly nothing and its features are not regenerated:
+    // once the margins of a logistic problem are large, sigma(-y z) underflows to 0 for every
+    // correctly classified sample.  (NaN coefficients, which mark invalid sample indices, are
+    // not zero and poison the row as before.)  The coefficient is the same for the whole
+    // workgroup, so the test is a scalar branch.
+    v4f a = v4f(0.f);
 #pragma unroll
     for (int b = 0; b < BMAX; ++b) {
         if (b < B) {
-            const v4f h = virtual_quad(mu, (uint32_t)q, i, (uint32_t)idx[(int64_t)i * B + b], k0, k1);
-            const double cb = coef[(int64_t)i * B + b];
-            a0 += cb * h.x;
-            a1 += cb * h.y;
-            a2 += cb * h.z;
-            a3 += cb * h.w;
+            const float cb = coef[(int64_t)i * B + b];
+            if (cb != 0.f) {
+                const v4f h = virtual_quad(mu, (uint32_t)q, i, (uint32_t)idx[(int64_t)i * B + b], k0, k1);
+                a += cb * h;
+            }
         }
     }
+    const float a0 = a.x, a1 = a.y, a2 = a.z, a3 = a.w;
     float* row = g + (int64_t)i * ld;
     if (vec_ok && c + 3 < d) {
         v4f out;
