@@ -69,7 +69,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="cfg3", help="primary workload: cfg3 or cfg4 (or cfg5 step-only)")
+    ap.add_argument("--config", default="cfg3",
+                    help="primary workload: cfg3 (default) or cfg4 for the bandwidth figure; cfg5, and the small cfg1 / cfg2 "
+                         "(launch-latency bound: their roofline block is context only), for profiles")
     ap.add_argument("--topology", default=None,
                     help="ring, expo1, grid, expo, none or full (default: first listed for the workload)")
     ap.add_argument("--also", default="cfg3:expo1,cfg4:expo1,cfg5:ring",
@@ -130,6 +132,15 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     if c["problem"] == "synthetic":
         sim.problem_synthetic(c["seed"], c["grad_var"])
         grad = sim.local_grad
+    elif c["problem"] == "lsq":  # cfg1: stored least-squares blocks, full batch
+        A, b, _ = inputs.lsq_problem(n, d, c["M"], c["seed"], c["noise_std"])
+        sim.problem_lsq(A, b)
+        grad = sim.local_grad
+    elif c["problem"] == "logreg":  # cfg2: stored logistic-regression features, minibatches drawn by the caller
+        feat, y, _ = inputs.logreg_problem(n, d, c["M"], c["seed"], c["mu_var"], c["label_noise_std"])
+        sim.problem_logreg(feat, y)
+        idx = sim.upload_batches(inputs.batch_indices(max(c["H"], 0) + steps + warmup, n, c["B"], c["M"], c["seed"]))
+        grad = lambda: sim.local_grad(idx[sim.k])
     else:  # cfg5: virtual-feature logistic regression
         y = inputs.virtual_labels(n, c["M"], c["seed"])
         sim.problem_logreg_virtual(c["seed"], y, c["mu_var"])

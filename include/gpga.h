@@ -202,8 +202,12 @@ gpga_status gpga_run(gpga_ctx* ctx, int64_t T, const int32_t* batch_table_dev, i
  * EINVAL if an index is out of range, a weight is negative or not finite, or a
  * row or column sum differs from 1 by more than 1e-5.  Synchronises the stream.
  * Gossip steps with GRID, EXPO and CUSTOM run as one fused kernel (the column
- * tile of all n rows staged in LDS, 20 B per element) while the tile fits in LDS;
- * above that they run as a local-update pass followed by a sparse product.  On
+ * tile of all n rows staged in LDS, 20 B per element) while the tile fits in LDS
+ * (n <= 256).  Above that, a W whose neighbours all lie within a circular distance
+ * band <= 32 of their node (n >= 4 band; the grid is one: band = its width) runs, on
+ * large problems, as a fused sliding-window kernel that keeps 4 band + 16 rows in LDS
+ * (still 20 B per element); any other W runs as a local-update pass followed by a
+ * sparse product (28 B per element).  On
  * every path g_dev is only read, and the array that held X^(k) holds unspecified
  * values after the step (as after any step: it is the target of the next one). */
 gpga_status gpga_set_mixing_csr(gpga_ctx* ctx, const int64_t* row_ptr_host, const int32_t* col_host,
@@ -284,6 +288,8 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * must not exceed "waves"), "row_lanes" (global-average kernel: lanes of a
  * wavefront spread over rows: 0 = automatic, 1, 2, 4), "xcd_swizzle" (0/1),
  * "mix_two_pass" (1 = sparse-W gossip steps always take the two-pass path),
+ * "mix_band" (sliding-window kernel for banded W: -1 = automatic (large problems whose
+ * column tile of all rows does not fit in LDS), 0 = never, 1 = whenever W qualifies),
  * "mix_waves" (sparse-W tile kernel: wavefronts per workgroup, 0 = automatic, 2, 4,
  * 8, 16), "mix_lane_bytes" (sparse-W tile kernel: widest lane type allowed,
  * 0 = automatic, 4, 8, 16), "small_run" (gpga_run on small problems: 1 = whole

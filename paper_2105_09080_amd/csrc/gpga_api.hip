@@ -2,6 +2,7 @@
 // schedule of Algorithm 1 (global average iff mod(k+1, H) == 0), the one-peer
 // offset schedule, scratch management and kernel dispatch.  All heavy work is
 // in the kernels; the host code here decides *which* fused kernel runs.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -89,6 +90,10 @@ void free_csr_device(gpga_ctx* c) {
     if (c->csr_ptr_d) (void)hipFree(c->csr_ptr_d);
     if (c->csr_col_d) (void)hipFree(c->csr_col_d);
     if (c->csr_val_d) (void)hipFree(c->csr_val_d);
+    if (c->csr_off_d) (void)hipFree(c->csr_off_d);
+    if (c->csr_ellval_d) (void)hipFree(c->csr_ellval_d);
+    c->csr_off_d = nullptr;
+    c->csr_ellval_d = nullptr;
     c->csr_ptr_d = nullptr;
     c->csr_col_d = nullptr;
     c->csr_val_d = nullptr;
@@ -109,6 +114,38 @@ gpga_status upload_csr(gpga_ctx* c) {
     if (e == hipSuccess) e = hipMemcpy(c->csr_ptr_d, c->csr.ptr.data(), np * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess && nz) e = hipMemcpy(c->csr_col_d, c->csr.col.data(), nz * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess && nz) e = hipMemcpy(c->csr_val_d, c->csr.val.data(), nz * sizeof(float), hipMemcpyHostToDevice);
+    // For the band kernel: circular offsets j - i of the neighbours and their weights, csr_max_row entries
+    // per row (padded with weight 0), so that a row's list is one address computation away.
+    c->csr_band = 0;
+    c->csr_max_row = 0;
+    for (int32_t i = 0; i < c->n; ++i) c->csr_max_row = std::max(c->csr_max_row, c->csr.ptr[i + 1] - c->csr.ptr[i]);
+    const size_t K = (size_t)(c->csr_max_row > 0 ? c->csr_max_row : 1);
+    std::vector<int32_t> off;
+    std::vector<float> wts;
+    const bool ell_ok = K <= 64 && K * (size_t)c->n <= ((size_t)1 << 26);
+    if (ell_ok) {
+        off.assign(K * (size_t)c->n, 0);
+        wts.assign(K * (size_t)c->n, 0.f);
+    }
+    for (int32_t i = 0; i < c->n; ++i) {
+        for (int32_t p2 = c->csr.ptr[i]; p2 < c->csr.ptr[i + 1]; ++p2) {
+            int32_t dlt = c->csr.col[p2] - i;                 // in (-n, n)
+            if (2 * dlt > c->n) dlt -= c->n;                   // shortest way round
+            if (2 * dlt < -c->n) dlt += c->n;
+            if (ell_ok) {
+                off[(size_t)i * K + (size_t)(p2 - c->csr.ptr[i])] = dlt;
+                wts[(size_t)i * K + (size_t)(p2 - c->csr.ptr[i])] = c->csr.val[p2];
+            }
+            const int32_t ad = dlt < 0 ? -dlt : dlt;
+            if (ad > c->csr_band) c->csr_band = ad;
+        }
+    }
+    if (ell_ok) {
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->csr_off_d), off.size() * sizeof(int32_t));
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->csr_ellval_d), wts.size() * sizeof(float));
+        if (e == hipSuccess) e = hipMemcpy(c->csr_off_d, off.data(), off.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->csr_ellval_d, wts.data(), wts.size() * sizeof(float), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         free_csr_device(c);
         return hip_fail(c, e, "mixing matrix upload");
@@ -772,6 +809,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "mix_two_pass")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "mix_two_pass must be 0 or 1");
         c->opt_mix_two_pass = (int)value;
+    } else if (!strcmp(name, "mix_band")) {
+        if (value < -1 || value > 1) return fail(c, GPGA_EINVAL, "mix_band must be -1 (automatic), 0 or 1");
+        c->opt_mix_band = (int)value;
     } else if (!strcmp(name, "small_run")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "small_run must be 0 or 1");
         c->opt_small_run = (int)value;
@@ -855,9 +895,9 @@ gpga_status gpga_query(gpga_ctx* c, const char* name, double* value_out) {
         // "pace_<field>:<kind>[/1]": state of the pacing controller of one kind of launch, for steps that read
         // the array bound as x (no suffix) or the one bound as x_new ("/1")
         const char* colon = strchr(name, ':');
-        static const char* kinds[] = {"global", "ring", "peer_long", "peer_8", "peer_4", "cycles", "self", "tile", "peer_16"};
+        static const char* kinds[] = {"global", "ring", "peer_long", "peer_8", "peer_4", "cycles", "self", "tile", "peer_16", "band"};
         int key = -1;
-        for (int j = 0; colon && j < 9; ++j) {
+        for (int j = 0; colon && j < 10; ++j) {
             const size_t kl = strlen(kinds[j]);
             if (!strncmp(colon + 1, kinds[j], kl) && (colon[1 + kl] == 0 || !strcmp(colon + 1 + kl, "/1")))
                 key = 2 * j + (colon[1 + kl] ? 1 : 0);

@@ -87,6 +87,7 @@ struct gpga_ctx {
     int opt_mix_lane_bytes = 0;  // sparse-W tile kernel: widest lane type allowed (0 = automatic, 4, 8, 16)
     int opt_mix_waves = 0;       // sparse-W tile kernel: wavefronts per workgroup (0 = automatic, 2, 4, 8, 16)
     int opt_mix_two_pass = 0;  // 1 = sparse-W steps always take the two-pass path
+    int opt_mix_band = -1;     // sliding-window kernel for banded W: -1 = automatic (large problems), 0 = never, 1 = whenever W qualifies
     int opt_mix_csr_lds = 1;   // 0 = the tile kernel reads W from global memory even when it fits in LDS
     int opt_small_run = 1;     // 0 = gpga_run never takes the single-workgroup path for small problems
     int opt_blocks_per_cu = -1;  // -1 = automatic, 0 = one workgroup per tile group, k = persistent
@@ -103,6 +104,10 @@ struct gpga_ctx {
     int32_t* csr_ptr_d = nullptr;  // device copies, library-owned
     int32_t* csr_col_d = nullptr;
     float* csr_val_d = nullptr;
+    int32_t* csr_off_d = nullptr;  // band kernel: signed circular offsets j - i (|offset| <= csr_band), csr_max_row per row
+    float* csr_ellval_d = nullptr; // band kernel: the weights in the same padded layout (padding has weight 0)
+    int32_t csr_band = 0;          // largest circular distance between a node and a neighbour: W is banded (mod n) with this half width
+    int32_t csr_max_row = 0;       // most entries in one row
     bool csr_ready = false;
 
     // step-size schedule gamma_k (evaluated on the host in double, stored as float)

@@ -265,6 +265,230 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
     pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
 }
 
+// Banded W (every neighbour within circular distance `band` of its node: rings with more taps, the
+// grid / torus, whose neighbours sit at distances 1 and the grid width): a sliding window instead
+// of the whole column tile.  The wavefronts of a workgroup take the rows of their column tile in
+// order, one row each per batch; y goes into a ring of 2*band + 2*waves rows in LDS, and output
+// row i is formed as soon as row i + band has arrived.  Rows 0 .. 2*band-1 of y are also kept
+// aside: the first `band` output rows wait for the last rows of the walk, and the last `band`
+// output rows wrap round to the first.  Every element of x, m, g is read once and m, x_new
+// written once (20 B per element) for any number of rows, LDS holds 4*band + 2*waves rows, and
+// the whole chip works on the same few rows at a time (persistent, paced), where the tile kernel
+// has every row of every array open at once.
+// The neighbour list of an output row (offset and weight, entry p in lane p; a fixed number of
+// entries per row, padded with weight 0, so that no row pointer has to be fetched first) travels
+// with the row loads of its batch, a few batches ahead; rows may have at most 64 neighbours.
+struct BandArgs {
+    StepGeom ge;
+    const int32_t* off;  // signed circular offsets j - i, K entries per row (padding: offset 0, weight 0)
+    const float* val;
+    int32_t K;
+    int64_t tiles;
+    int32_t band;
+    int32_t ring_rows;   // 2*band + 2*waves
+    PaceArgs pace;
+};
+
+constexpr int kBandDepth = 4;    // row batches in flight per wavefront, the one being mixed included
+constexpr int kBandTailMax = 8;  // tail output rows per wavefront: 2*band <= kBandTailMax * waves
+
+template <typename T, int MOM>
+__global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
+    constexpr int V = sizeof(T) / sizeof(float);
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    T* __restrict__ ring = reinterpret_cast<T*>(s_raw);            // [ring_rows][kWave]
+    T* __restrict__ head = ring + (size_t)a.ring_rows * kWave;     // [2*band][kWave]: y of the first rows
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NW = blockDim.x >> 6;
+    const int n = a.ge.n, band = a.band, RB = a.ring_rows;
+    const int64_t ldT = a.ge.ld / V;
+    const float lr = a.ge.lr, mu = a.ge.mu;
+    constexpr uint32_t kRowUnits = MOM ? 5u : 3u;
+    const PaceRun run = pace_begin(a.pace, lane);
+    uint32_t units_done = 0;
+    const int nb = (n + NW - 1) / NW;  // batches of NW rows
+
+    struct Row {
+        T xv, mv, gv;
+    };
+    struct Taps {  // neighbour list of one output row: entry p in lane p
+        int off;
+        float val;
+        int cnt;
+    };
+
+    for (int64_t tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+        const int64_t col = tile * kWave + lane;
+        const bool on = col < a.ge.ncols;
+        const T* __restrict__ xp = reinterpret_cast<const T*>(a.ge.x + a.ge.col0) + col;
+        const T* __restrict__ gp = reinterpret_cast<const T*>(a.ge.g + a.ge.col0) + col;
+        T* __restrict__ mp = MOM ? reinterpret_cast<T*>(a.ge.m + a.ge.col0) + col : nullptr;
+        T* __restrict__ xnp = reinterpret_cast<T*>(a.ge.x_new + a.ge.col0) + col;
+
+        auto load_row = [&](Row& r, int row) {  // row is the same for the whole wavefront
+            if (row < n && on) {
+                const int64_t o = (int64_t)row * ldT;
+                r.xv = ld_stream(xp + o);
+                if (MOM) r.mv = ld_stream(mp + o);
+                r.gv = ld_stream(gp + o);
+            }
+        };
+        auto load_taps = [&](Taps& t, int i) {  // i uniform; rows outside [0, n) have no taps
+            t.off = 0;
+            t.val = 0.f;
+            t.cnt = 0;
+            if (i >= 0 && i < n) {
+                t.cnt = a.K;
+                if (lane < a.K) {
+                    t.off = a.off[(int64_t)i * a.K + lane];
+                    t.val = a.val[(int64_t)i * a.K + lane];
+                }
+            }
+        };
+        // sum_j w_ij y_j for output row i; `fetch(j)` returns y of (unwrapped) row i + offset
+        auto mix = [&](const Taps& t, auto fetch) -> T {
+            T acc = T(0);
+            const int cnt = __builtin_amdgcn_readfirstlane(t.cnt);
+            for (int q = 0; q < cnt; ++q) {
+                const int dj = __builtin_amdgcn_readlane(t.off, q);
+                const float wv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t.val), q));
+                acc += wv * fetch(dj);
+            }
+            return acc;
+        };
+
+        // neighbour lists of this wavefront's tail rows (the last `band` and the first `band` output rows),
+        // fetched before anything else of the tile
+        Taps tail[kBandTailMax];
+#pragma unroll
+        for (int m = 0; m < kBandTailMax; ++m) {
+            const int k = wave + m * NW;  // k < band: output row n - band + k;  band <= k < 2*band: output row k - band
+            load_taps(tail[m], k < band ? n - band + k : (k < 2 * band ? k - band : -1));
+        }
+
+        // Rows and neighbour lists run kBandDepth - 1 batches ahead of the batch being mixed: a batch ends
+        // in a workgroup barrier, and with a single batch of look-ahead every barrier exposed one memory
+        // latency (measured: 2.8 us per batch whatever the pacing rate).  The buffers rotate through a loop
+        // unrolled kBandDepth times, so every index is a constant.
+        Row rows[kBandDepth];
+        Taps taps[kBandDepth];
+        // HOT: nothing in the batch is conditional (whole tile, whole batches, every wavefront has an output
+        // row whose window lies inside the walk).  Only then can the wait for a batch's data leave exactly the
+        // younger loads and stores outstanding; a store under a condition makes that count uncertain and the
+        // wait falls back to "everything", which empties the pipeline.
+        auto fetch_batch = [&](auto hot, Row& r, Taps& tp, int t) {  // batch t: row t*NW + wave and the list of its output row
+            constexpr bool HOT = decltype(hot)::value;
+            if (HOT) {
+                const int row = t * NW + wave;
+                const int64_t e = (int64_t)(row - band) * a.K + (lane < a.K ? lane : 0);
+                tp.off = a.off[e];
+                tp.val = a.val[e];
+                tp.cnt = a.K;
+                pace_wait(run, units_done);
+                units_done += kRowUnits;
+                const int64_t o = (int64_t)row * ldT;
+                r.xv = ld_stream(xp + o);
+                if (MOM) r.mv = ld_stream(mp + o);
+                r.gv = ld_stream(gp + o);
+            } else if (t < nb) {
+                load_taps(tp, t * NW + wave - band);
+                pace_wait(run, units_done);
+                units_done += kRowUnits;
+                load_row(r, t * NW + wave);
+            }
+        };
+        int sb = 0;  // ring slot of the first row of the current batch: (t * NW) mod RB
+        auto batch = [&](auto hot, const Row& cur, const Taps& tp, Row& ahead_r, Taps& ahead_t, int t) {
+            constexpr bool HOT = decltype(hot)::value;
+            fetch_batch(hot, ahead_r, ahead_t, t + kBandDepth - 1);
+            __builtin_amdgcn_sched_barrier(0);  // keep the issue order: loads, then stores
+            const int row = t * NW + wave;
+            if (HOT || row < n) {
+                T y = T(0);
+                if (HOT || on) {
+                    T mom = cur.gv;
+                    if (MOM) {
+                        mom = mu * cur.mv + cur.gv;
+                        st_stream(mp + (int64_t)row * ldT, mom);
+                    }
+                    y = half_step<MOM>(cur.xv, cur.gv, mom, lr, mu);
+                }
+                int slot = sb + wave;
+                if (slot >= RB) slot -= RB;
+                ring[slot * kWave + lane] = y;
+                if (!HOT && row < 2 * band) head[row * kWave + lane] = y;
+            }
+            __syncthreads();  // rows < (t + 1) * NW are in the ring
+            const int i = row - band;  // this wavefront's output row: its window ends at row i + band = row
+            if (HOT || (i >= band && row < n)) {
+                const T acc = mix(tp, [&](int dj) -> T {
+                    int slot = sb + wave - band + dj;  // in [-2*band, RB + NW)
+                    if (slot < 0) slot += RB;
+                    if (slot >= RB) slot -= RB;
+                    return ring[slot * kWave + lane];
+                });
+                if (HOT || on) st_stream(xnp + (int64_t)i * ldT, acc);
+            }
+            sb += NW;
+            if (sb >= RB) sb -= RB;
+        };
+        const bool whole_tile = (tile + 1) * kWave <= a.ge.ncols;
+        const int nb_full = n / NW;                        // batches whose rows all exist
+        const int t_hot = (2 * band + NW - 1) / NW;        // from this batch on every wavefront has an output row
+#pragma unroll
+        for (int j = 0; j < kBandDepth - 1; ++j) fetch_batch(std::false_type{}, rows[j], taps[j], j);
+        // all kBandDepth batches of a hot round, and the batches they fetch ahead, are whole and past the start
+        auto is_hot = [&](int t0) { return whole_tile && t0 >= t_hot && t0 + 2 * kBandDepth - 2 < nb_full; };
+        for (int t0 = 0; t0 < nb;) {
+            if (is_hot(t0)) {
+                // consecutive hot rounds form a loop of their own: its only other predecessor is itself, so the
+                // outstanding loads and stores are known exactly at every wait from the second round on
+                do {
+#pragma unroll
+                    for (int j = 0; j < kBandDepth; ++j)
+                        batch(std::true_type{}, rows[j], taps[j], rows[(j + kBandDepth - 1) % kBandDepth],
+                              taps[(j + kBandDepth - 1) % kBandDepth], t0 + j);
+                    t0 += kBandDepth;
+                } while (is_hot(t0));
+            } else {
+#pragma unroll
+                for (int j = 0; j < kBandDepth; ++j) {
+                    if (t0 + j >= nb) break;
+                    batch(std::false_type{}, rows[j], taps[j], rows[(j + kBandDepth - 1) % kBandDepth],
+                          taps[(j + kBandDepth - 1) % kBandDepth], t0 + j);
+                }
+                t0 += kBandDepth;
+            }
+        }
+        // Tail: output rows n - band .. n - 1 wrap round to the first rows of y (kept aside), output rows
+        // 0 .. band - 1 reach back to the last rows of the walk (still in the ring).
+        const int sb_last = sb - NW;           // may be negative: slot of row (nb - 1) * NW, modulo RB
+        const int row_last0 = (nb - 1) * NW;   // the row that slot belongs to
+        auto ring_row = [&](int r) -> T {      // r in [n - 2*band, n)
+            int slot = sb_last + (r - row_last0);
+            while (slot < 0) slot += RB;
+            if (slot >= RB) slot -= RB;
+            return ring[slot * kWave + lane];
+        };
+#pragma unroll
+        for (int m = 0; m < kBandTailMax; ++m) {
+            const int k = wave + m * NW;
+            if (k >= 2 * band) break;
+            const int i = k < band ? n - band + k : k - band;
+            const T acc = mix(tail[m], [&](int dj) -> T {
+                const int j = i + dj;
+                if (j >= n) return head[(j - n) * kWave + lane];
+                if (j < 0) return ring_row(j + n);
+                return k < band ? ring_row(j) : head[j * kWave + lane];
+            });
+            if (on) st_stream(xnp + (int64_t)i * ldT, acc);
+        }
+        __syncthreads();  // the next tile overwrites the ring and the kept rows
+    }
+    pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
+}
+
 // Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  One workgroup = one row of one
 // column tile (256 lanes).  Workgroup ids are dealt to the 8 XCDs round-robin, each
 // with its own L2; the id is remapped so that all rows of a tile run on ONE XCD, in
@@ -304,18 +528,24 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
     pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
-    // Default: one workgroup per tile.  On request ("pace_gbs" / "blocks_per_cu" options) exactly
-    // the resident workgroups, striding over the tiles and paced.  Measured on the n = 64,
-    // d = 25.6M shape the paced form is bimodal (5.0-5.1 TB/s at most targets, 5.5-5.7 TB/s at
-    // isolated ones) against a steady 5.2-5.3 TB/s one-shot, so it is not the default.
-    const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : 0.0;
-    const int want = c->opt_blocks_per_cu < 0 ? (gbs > 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
+    // Large problems: exactly the resident workgroups, striding over the tiles and paced at the rate the
+    // controller of this kind of launch has found: all workgroups then read the same row group of their
+    // tiles at the same time and later store the same output rows, so the chip alternates between a pure
+    // read phase and a pure write phase over a few rows at a time.  Small problems, or pacing switched
+    // off: one workgroup per tile.
+    const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20) && sizeof(T) >= 8;
+    const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : (c->opt_pace_gbs < 0 && big ? -1.0 : 0.0);
+    const int want = c->opt_blocks_per_cu < 0 ? (gbs != 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
     if (want > 0) {
         int occ = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM, LCSR, TRACE>, threads, lds) != hipSuccess || occ < 1)
             occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
-        if (resident < blocks) blocks = resident;
+        if (resident < blocks) {
+            const int64_t rounds = (a.tiles + resident - 1) / resident;  // whole rounds: see launch_planned
+            const int64_t even = (a.tiles + rounds - 1) / rounds;
+            blocks = (even * 8 >= resident * 7) ? even : resident;
+        }
         pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_TILE, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
     hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR, TRACE>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
@@ -375,6 +605,65 @@ hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& 
     return hipGetLastError();
 }
 
+// Whether the banded kernel can take this W, and with which lane type: the ring of 2*band + 2*waves rows
+// plus the 2*band kept rows must fit in LDS (at least two workgroups per compute unit), the window must
+// not overlap itself (n >= 4*band), and the tail rows must fit the per-wavefront lists.
+template <typename T, int MOM>
+hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds) {
+    const int threads = kWave * waves;
+    int64_t blocks = a.tiles;
+    pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
+    const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20);
+    const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : (c->opt_pace_gbs < 0 && big ? -1.0 : 0.0);
+    const int want = c->opt_blocks_per_cu < 0 ? (big || gbs != 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
+    static bool attr_set = false;  // per instantiation: allow more than the default 64 KiB of dynamic LDS
+    if (!attr_set && lds > 48 * 1024) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_step_band<T, MOM>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->max_lds_block);
+        attr_set = true;
+    }
+    if (want > 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_band<T, MOM>, threads, lds) != hipSuccess || occ < 1) occ = 1;
+        const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
+        if (resident < blocks) {
+            const int64_t rounds = (a.tiles + resident - 1) / resident;  // whole rounds, as for the stencil kernels
+            const int64_t even = (a.tiles + rounds - 1) / rounds;
+            blocks = (even * 8 >= resident * 7) ? even : resident;
+        }
+        pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_BAND, (double)blocks * waves, (int)sizeof(T), &a.pace);
+    }
+    hipLaunchKernelGGL((k_step_band<T, MOM>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_band(const gpga_ctx* c, const StepGeom& ge, int mom, int waves) {
+    BandArgs a;
+    a.ge = ge;
+    a.off = c->csr_off_d;
+    a.val = c->csr_ellval_d;
+    a.K = c->csr_max_row;
+    a.tiles = (ge.ncols + kWave - 1) / kWave;
+    a.band = c->csr_band;
+    a.ring_rows = 2 * c->csr_band + 2 * waves;
+    const size_t lds = (size_t)(a.ring_rows + 2 * c->csr_band) * kWave * sizeof(T);
+    if (mom == 2) return launch_band_mom<T, 2>(c, a, waves, lds);
+    return mom == 1 ? launch_band_mom<T, 1>(c, a, waves, lds) : launch_band_mom<T, 0>(c, a, waves, lds);
+}
+
+// 0 = W does not qualify, else the lane bytes (16, 8 or 4) the banded kernel would run with.
+int band_lane_bytes(const gpga_ctx* c, int vec, int waves) {
+    const int band = c->csr_band;
+    if (band < 1 || c->csr_max_row > kWave || c->n < 4 * band || 2 * band > kBandTailMax * waves || !c->csr_off_d) return 0;
+    const size_t rows = (size_t)(4 * band + 2 * waves);
+    const size_t budget = (size_t)c->max_lds_block / 2;  // two workgroups per compute unit
+    const int cap = vec == 4 ? (c->opt_mix_lane_bytes ? c->opt_mix_lane_bytes : 16) : 4;
+    for (int bytes = cap; bytes >= 4; bytes /= 2)
+        if (rows * kWave * (size_t)bytes <= budget) return bytes;
+    return 0;
+}
+
 }  // namespace
 
 hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, double* spread_partials,
@@ -387,6 +676,24 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, doubl
     const size_t n = (size_t)ge.n;
     const bool two_pass = c->opt_mix_two_pass == 1;
     const size_t lane_cap = c->opt_mix_lane_bytes ? (size_t)c->opt_mix_lane_bytes : 16;
+    // Banded W with more rows than the whole-tile kernel can stage (or on request): the sliding-window
+    // kernel.  Where the whole tile fits, the tile kernel is the faster of the two (measured on n = 64,
+    // d = 25.6M, grid: 5.29 TB/s against 5.0) and also fuses the consensus trace.
+    const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20);
+    const bool tile_fits = n * kWave * sizeof(float) <= kTileLdsBytes;
+    const int band_waves = 8;
+    const int band_bytes = (!two_pass && c->opt_mix_band != 0 && (c->opt_mix_band == 1 || (big && !tile_fits)))
+                               ? band_lane_bytes(c, vec, band_waves) : 0;
+    if (band_bytes) {
+        StepGeom g2 = ge;
+        if (vec == 4 && band_bytes == 16) return launch_band<v4f>(c, ge, mom, band_waves);
+        if (vec == 4 && band_bytes == 8) {
+            g2.ncols = ge.ncols * 2;
+            return launch_band<v2f>(c, g2, mom, band_waves);
+        }
+        if (vec == 4) g2.ncols = ge.ncols * 4;
+        return launch_band<float>(c, g2, mom, band_waves);
+    }
     if (vec == 4) {
         // widest lane type whose n x 64-lane tile fits in LDS (16-byte aligned rows also
         // satisfy the narrower types)

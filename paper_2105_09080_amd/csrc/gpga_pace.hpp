@@ -64,7 +64,7 @@ struct PaceState {             // 64 bytes, device memory owned by the context, 
 static_assert(sizeof(PaceState) == 64, "PaceState is one 64-byte line");
 
 enum PaceKey : int {           // launches of one kind share a PaceState ...
-    PACE_GLOBAL = 0, PACE_RING, PACE_PEER_LONG, PACE_PEER_8, PACE_PEER_4, PACE_CYCLES, PACE_SELF, PACE_TILE, PACE_PEER_16,
+    PACE_GLOBAL = 0, PACE_RING, PACE_PEER_LONG, PACE_PEER_8, PACE_PEER_4, PACE_CYCLES, PACE_SELF, PACE_TILE, PACE_PEER_16, PACE_BAND,
     kPaceKinds = 16,
     // ... per direction of the x / x_new ping-pong: which of the two bound arrays a step reads and which it
     // writes changes the rate the memory system sustains (by up to 8 % for some placements of the arrays),

@@ -206,3 +206,78 @@ def test_logistic_trajectory_on_the_appendix_topologies(hx, topology):
     assert_close(host(sim.X), ref.X, TOL_FINAL, "final iterate")
     assert all(cons[k] <= 1e-6 * np.linalg.norm(ref.X) for k in range(H - 1, T, H))   # zero right after each average
     sim.close()
+
+
+def banded(n, band, seed):
+    """Random doubly stochastic W whose neighbours all lie within circular distance `band`:
+    a convex combination of cyclic shifts by -band .. band (a circulant; every shift is a permutation)."""
+    rng = np.random.default_rng(seed)
+    shifts = np.arange(-band, band + 1)
+    w = rng.random(len(shifts)) * (rng.random(len(shifts)) < 0.7)
+    w[band] += 0.2                        # self weight
+    w[0] += 0.05                          # keep the band as wide as asked for
+    w /= w.sum()
+    W = sum(wk * np.roll(np.eye(n), s, axis=1) for wk, s in zip(w, shifts))
+    return W.astype(np.float32).astype(np.float64)
+
+
+BAND_CASES = [
+    # n, d, ld_pad, topology (or band of a custom circulant), momentum, nesterov
+    (20, 515, 1, "grid", 0.9, False),            # 4 x 5 torus: band 5 = n / 4, vector path plus a tail
+    (25, 300, 0, "grid", 0.0, False),            # 5 x 5
+    (64, 4100, 0, "grid", 0.9, False),           # 8 x 8, 16-byte lanes
+    (64, 4102, 2, "grid", 0.9, True),            # rows not 16-byte aligned: 4-byte lanes
+    (100, 2052, 0, "grid", 0.9, True),           # 10 x 10
+    (256, 1000, 0, "grid", 0.9, False),          # 16 x 16
+    (1024, 2052, 0, "grid", 0.9, False),         # 32 x 32: band 32, the kept rows and the ring hold 144 rows
+    (1023, 700, 0, "grid", 0.5, False),          # 31 x 33: n not a multiple of the wavefronts per workgroup
+    (37, 900, 0, 1, 0.9, False),                 # a ring with random weights
+    (50, 1234, 0, 3, 0.9, False),
+    (333, 640, 0, 7, 0.9, True),
+    (2000, 260, 0, 32, 0.0, False),              # the widest band the kernel takes
+]
+
+
+@pytest.mark.parametrize("n,d,pad,topology,momentum,nesterov", BAND_CASES)
+def test_banded_W_sliding_window_kernel_matches_oracle(hx, n, d, pad, topology, momentum, nesterov):
+    X, Mb, G = inputs.random_state(n, d, seed=9000 + n + d)
+    lr = 0.37
+    W = banded(n, topology, seed=n) if isinstance(topology, int) else None
+    name = "custom" if W is not None else topology
+    sim = hx.Simulation(n, d, topology=name, H=0, lr=lr, momentum=momentum, ld=d + pad)
+    if W is not None:
+        sim.set_mixing(W)
+    if nesterov:
+        sim.set_nesterov(True)
+    sim.set_option("mix_band", 1)
+    X_ref, M_ref = X, (Mb if momentum else np.zeros_like(Mb))
+    sim.set_state(X=X, M=Mb, G=G, k=0)
+    for k in range(2):          # two steps: both directions of the ping-pong
+        sim.step()
+        X_ref, M_ref = orc.gossip_pga_step(X_ref, M_ref, G, k, topology=name, H=0, lr=lr, momentum=momentum,
+                                           nesterov=nesterov, W=W)
+        X_ref = X_ref.astype(np.float32).astype(np.float64)
+        M_ref = M_ref.astype(np.float32).astype(np.float64)
+        assert_close(host(sim.X), X_ref, TOL_STEP, f"X after step {k}")
+        if momentum:
+            assert_close(host(sim.M), M_ref, TOL_STEP, f"M after step {k}")
+    np.testing.assert_array_equal(host(sim.G), G.astype(np.float64))      # the gradients are only read
+    sim.close()
+
+
+@pytest.mark.parametrize("opts", [{"blocks_per_cu": 1}, {"blocks_per_cu": 2, "pace_gbs": 3000}, {"mix_lane_bytes": 8},
+                                  {"mix_lane_bytes": 4, "pace_gbs": 8000}],
+                         ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
+def test_banded_kernel_persistent_and_paced(hx, opts):
+    n, d = 64, 300_004          # more column tiles than resident workgroups
+    X, Mb, G = inputs.random_state(n, d, seed=77)
+    sim = hx.Simulation(n, d, topology="grid", H=0, lr=0.1, momentum=0.9)
+    sim.set_option("mix_band", 1)
+    for name, v in opts.items():
+        sim.set_option(name, v)
+    sim.set_state(X=X, M=Mb, G=G, k=0)
+    sim.step()
+    X_ref, M_ref = orc.gossip_pga_step(X, Mb, G, 0, topology="grid", H=0, lr=0.1, momentum=0.9)
+    assert_close(host(sim.X), X_ref, TOL_STEP, "X")
+    assert_close(host(sim.M), M_ref, TOL_STEP, "M")
+    sim.close()
