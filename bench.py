@@ -34,9 +34,14 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 # These are constants copied from those summaries, NOT something a bench run measures: the JSON line
 # carries them as `traffic` together with `traffic_source`.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3/ring": (32768370216, "profiles/step_walk_cfg3_ring.md"),     # 12.000 B fetched + 8.000 B written per element
-    "cfg4/expo1": (140803063107, "profiles/step_cfg4_expo1.md"),       # k_step_walk, all five offsets
-    "cfg3/grid": (32768074151, "profiles/step_tile_cfg3_grid.md"),     # k_step_tile
+    # 12.000 B fetched + 8.000 B written per element in every case; where several kernels share the gossip steps
+    # (one per one-peer offset class) the largest of their per-launch figures is given
+    "cfg3/ring": (32768461457, "profiles/step_cfg3_ring.md"),          # k_step_walk
+    "cfg3/expo1": (32768542291, "profiles/step_cfg3_expo1.md"),        # k_step_walk (offsets 1, 2), k_step_cycles (4 .. 32)
+    "cfg4/expo1": (140800613762, "profiles/step_cfg4_expo1.md"),       # k_step_walk (offset 1), k_step_cycles (2 .. 16)
+    "cfg5/ring": (20480466145, "profiles/step_cfg5_ring.md"),          # k_step_walk with the consensus trace riding along
+    "cfg3/grid": (32769277532, "profiles/step_sparse_cfg3_grid.md"),   # k_step_tile
+    "cfg5/grid": (20480833456, "profiles/step_sparse_cfg5_grid.md"),   # k_step_band
 }
 
 
@@ -56,12 +61,14 @@ PAPER_CONTEXT = {
 
 
 def gossip_kernel_name(topology, n):
-    """Which fused kernel runs the gossip steps of this workload."""
-    if topology in ("ring", "expo1", "none"):
+    """Which fused kernels run the gossip steps of this workload."""
+    if topology in ("ring", "none"):
         return "k_step_walk"
+    if topology == "expo1":
+        return "k_step_walk for cycles longer than 16 rows, k_step_cycles for cycles of 2 .. 16 rows"
     if topology == "full":
         return "k_step_global"
-    return "k_step_tile" if n <= 256 else "k_update_y + k_spmm_rows"
+    return "k_step_tile" if n <= 256 else "k_step_band where W is banded, else k_update_y + k_spmm_rows"
 
 
 def parse_args():
