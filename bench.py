@@ -221,7 +221,7 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     res["consensus_error_final"] = sim.consensus_error()
     # where the pacing controllers of the persistent launches ended up (device-side state, read back once)
     res["pace_controllers"] = {}
-    for kind in [k + d for k in ("ring", "global", "peer_long", "peer_16", "peer_8", "peer_4", "cycles") for d in ("", "/1")]:
+    for kind in [k + d for k in ("ring", "global", "peer_long", "peer_16", "peer_8", "peer_4", "cycles", "tile", "band", "self") for d in ("", "/1")]:
         launches = sim.query(f"pace_launches:{kind}")
         if launches > 0:
             res["pace_controllers"][kind] = {

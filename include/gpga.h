@@ -295,8 +295,8 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * 0 = automatic, 4, 8, 16), "small_run" (gpga_run on small problems: 1 = whole
  * iterations in single-workgroup launches (default), 0 = one kernel per stage),
  * "mix_csr_lds" (sparse-W tile kernel: 1 = copy a small W
- * into LDS (default), 0 = read it from global memory), "cycle_kernel" (whole-cycle kernel for one-peer offset
- * n/2: -1 = automatic (large problems), 0 = never, 1 = always),
+ * into LDS (default), 0 = read it from global memory), "cycle_kernel" (row-streaming kernel for one-peer
+ * steps whose cycles have 2, 4, 8 or 16 rows: -1 = automatic (large problems), 0 = never, 1 = always),
  * "pace_min_cycle" (shortest row cycle whose walk is paced, 0 = automatic (4)),
  * "blocks_per_cu" (persistent launch of the fused step: -1 = automatic, 0 = one
  * workgroup per column-tile group, k = 1..32 resident workgroups per compute unit,

@@ -94,7 +94,7 @@ struct gpga_ctx {
     int num_cus = 256;
     int max_lds_block = 64 * 1024;  // LDS bytes one workgroup may ask for on this device
     int opt_pace_gbs = -1;   // target GB/s of paced persistent launches: -1 = automatic, 0 = off
-    int opt_cycle_kernel = -1;   // whole-cycle kernel for one-peer cycles of 2 / 4 rows: -1 automatic, 0 never, 1 always
+    int opt_cycle_kernel = -1;   // row-streaming kernel for one-peer cycles of 2 .. 16 rows: -1 automatic, 0 never, 1 always
     int opt_pace_min_cycle = 0;  // shortest row cycle that is paced (0 = automatic)
     double clock_hz = 1e8;   // rate of the constant chip clock read by the pacing code
     PaceState* pace_states = nullptr;  // kPaceKeys controller states in device memory, library-owned

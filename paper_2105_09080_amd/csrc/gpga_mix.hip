@@ -616,11 +616,14 @@ hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds)
     const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20);
     const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : (c->opt_pace_gbs < 0 && big ? -1.0 : 0.0);
     const int want = c->opt_blocks_per_cu < 0 ? (big || gbs != 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
-    static bool attr_set = false;  // per instantiation: allow more than the default 64 KiB of dynamic LDS
-    if (!attr_set && lds > 48 * 1024) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_step_band<T, MOM>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->max_lds_block);
-        attr_set = true;
+    // per instantiation and device: allow more than the default 64 KiB of dynamic LDS (setting it twice is harmless)
+    static bool attr_set[64] = {false};
+    const int dev = c->device >= 0 && c->device < 64 ? c->device : 0;
+    if (!attr_set[dev] && lds > 48 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_step_band<T, MOM>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->max_lds_block);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
     }
     if (want > 0) {
         int occ = 0;

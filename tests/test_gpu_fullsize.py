@@ -2,8 +2,8 @@
 
 * cfg3 / cfg4 shapes: ONE fused step per kernel variant compared with the oracle on
   EVERY element (all n x d of X and M), in column chunks: the paced ring walk, the
-  paced one-peer walks over long, 8-row and 4-row cycles, the whole-cycle kernel
-  (offset n/2) and the global average.  The oracle's step needs no random numbers
+  paced one-peer walk over long cycles, the row-streaming kernel over cycles of 16, 8,
+  4 and 2 rows and the global average.  The oracle's step needs no random numbers
   (it is advanced from the GPU's own X, M, G), so a chunk is a few BLAS calls.
 * cfg5 at its full shape (n = 1024, d = 10^6, virtual features), H = 8, 2H + 1 steps
   per topology, every step in lock-step: complete gradient rows of eight nodes spread
@@ -99,9 +99,11 @@ CFG3_VARIANTS = [
     ("ring", 0, "paced ring walk"),
     ("ring", 47, "global average"),
     ("expo1", 0, "paced one-peer walk, offset 1 (one cycle of 64 rows)"),
-    ("expo1", 3, "paced one-peer walk, offset 8 (cycles of 8 rows)"),
-    ("expo1", 4, "paced one-peer walk, offset 16 (cycles of 4 rows)"),
-    ("expo1", 5, "whole-cycle kernel, offset 32 (cycles of 2 rows)"),
+    ("expo1", 1, "paced one-peer walk, offset 2 (two cycles of 32 rows)"),
+    ("expo1", 2, "row-streaming kernel, offset 4 (cycles of 16 rows)"),
+    ("expo1", 3, "row-streaming kernel, offset 8 (cycles of 8 rows)"),
+    ("expo1", 4, "row-streaming kernel, offset 16 (cycles of 4 rows)"),
+    ("expo1", 5, "row-streaming kernel, offset 32 (cycles of 2 rows)"),
 ]
 
 
