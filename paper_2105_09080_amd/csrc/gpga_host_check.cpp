@@ -1,6 +1,7 @@
 // Host-only check program for the parts of libgpga that never touch the GPU: the graph
 // builders, the validation of a caller's mixing matrix, the connectivity estimate beta
-// (Assumption 3) and the schedule arithmetic of Algorithm 1.  It is compiled from the very
+// (Assumption 3), the schedule arithmetic of Algorithm 1 and the controller that sets the
+// rate of paced launches (run here against a model of a launch).  It is compiled from the very
 // sources the library uses, with AddressSanitizer and UndefinedBehaviorSanitizer on the host
 // side, and run by the CPU test suite: the sanitizers abort the run on any bad access, the
 // printed values are compared with the oracle by the test.
@@ -14,6 +15,7 @@
 #include <vector>
 
 #include "gpga_internal.hpp"
+#include "gpga_pace.hpp"
 #include "gpga_schedule.hpp"
 
 namespace {
@@ -156,6 +158,94 @@ void rejected_matrices() {
     }
 }
 
+// The pacing controller against a model of what the kernels measure.  A launch at rate r on a
+// machine whose memory system sustains E for that kernel: up to E its slowest wavefront ends
+// 40-65 us after its last deadline, and one launch in ten is late for no reason (150 us);
+// above E it falls behind by 75 us per percent of excess.  The clock runs at 100 MHz; a launch
+// moves the 32.768 GB of the 64 x 25.6M fused step.
+struct PaceModel {
+    std::mt19937 rng;
+    double edge_gbs;
+    explicit PaceModel(unsigned seed, double e) : rng(seed), edge_gbs(e) {}
+    double uniform() { return (double)(rng() >> 8) / 16777216.0; }
+    uint32_t lateness(double rate_gbs) {
+        double us = 40.0 + 25.0 * uniform();
+        if (rate_gbs > edge_gbs) us += (rate_gbs / edge_gbs - 1.0) * 100.0 * 75.0 + 20.0 * uniform();
+        else if (uniform() < 0.1) us = 150.0;
+        return (uint32_t)(us * 100.0);
+    }
+};
+
+void pace_controller_model() {
+    const double clock_hz = 1e8, bytes = 32.768e9;
+    const double fp = 1e9 / clock_hz * 16.0;  // rate units per GB/s
+    for (unsigned seed = 1; seed <= 6; ++seed) {
+        const double e0 = 6150.0 + 70.0 * seed;  // 6220 .. 6570 GB/s
+        PaceModel model(seed, e0);
+        PaceState st{};
+        PaceArgs p{};
+        p.st = &st;
+        p.rate_fixed_fp = 0;
+        p.rate_init_fp = (uint32_t)(kPaceInitGbs * fp);
+        p.rate_min_fp = (uint32_t)(1000.0 * fp);
+        p.rate_max_fp = (uint32_t)(kPaceMaxGbs * fp);
+        p.late_floor = (uint32_t)(kPaceLateFloorSeconds * clock_hz);
+        int settle = -1, drop_recover = -1, rise_recover = -1, over = 0, counted = 0;
+        double settled_rate = 0.0, sum_rate = 0.0;
+        const int kDrop = 300, kRise = 600, kEnd = 900;
+        for (int launch = 0; launch < kEnd; ++launch) {
+            if (launch == kDrop) model.edge_gbs = e0 * 0.94;
+            if (launch == kRise) model.edge_gbs = e0 * 0.94 * 1.05;
+            const uint32_t r = st.rate_fp ? st.rate_fp : p.rate_init_fp;  // what pace_begin would take
+            const double gbs = r / fp;
+            const uint32_t plan = (uint32_t)(bytes / (gbs * 1e9) * clock_hz);
+            pace_controller(p, r, model.lateness(gbs), plan);
+            if (!st.rate_fp) st.rate_fp = r;  // a launch whose lateness decided nothing leaves the rate alone
+            expect(st.rate_fp >= p.rate_min_fp && st.rate_fp <= p.rate_max_fp, "rate inside its range");
+            if (settle < 0 && st.hold > 0) {
+                settle = launch + 1;
+                settled_rate = st.rate_fp / fp;
+            }
+            if (launch >= 60 && launch < kDrop) {
+                sum_rate += gbs;
+                ++counted;
+                if (gbs > 1.015 * e0) ++over;
+            }
+            if (launch >= kDrop && drop_recover < 0 && gbs <= 1.0075 * model.edge_gbs) drop_recover = launch - kDrop;
+            if (launch >= kRise && rise_recover < 0 && gbs >= 0.985 * model.edge_gbs) rise_recover = launch - kRise;
+        }
+        const double mean_rate = sum_rate / counted;
+        std::printf("pace_model %u edge %.0f settle %d settled_rate %.0f mean_rate %.0f over %d of %d drop_recover %d rise_recover %d\n",
+                    seed, e0, settle, settled_rate, mean_rate, over, counted, drop_recover, rise_recover);
+        expect(settle > 0 && settle <= 48, "the controller brackets the edge within 48 launches");
+        // two late launches in a row for no reason (one pair in a hundred) can end the first search early:
+        // the first hold may start a few percent low, the short first hold and the next search repair it
+        expect(settled_rate >= 0.96 * e0 && settled_rate <= 1.012 * e0, "the first held rate is near the edge");
+        expect(mean_rate >= 0.985 * e0 && mean_rate <= 1.012 * e0, "the mean rate while holding sits at the edge");
+        expect(over * 20 <= counted, "at most one launch in twenty runs more than 1.5 % past the edge");
+        expect(drop_recover >= 0 && drop_recover <= 12, "a lower edge is followed within 12 launches");
+        expect(rise_recover >= 0 && rise_recover <= 80, "a higher edge is found after the hold runs out");
+    }
+    // an edge beyond the range: the rate stops at the upper limit
+    {
+        PaceModel model(99, 9500.0);
+        PaceState st{};
+        PaceArgs p{};
+        p.st = &st;
+        p.rate_init_fp = (uint32_t)(kPaceInitGbs * fp);
+        p.rate_min_fp = (uint32_t)(1000.0 * fp);
+        p.rate_max_fp = (uint32_t)(kPaceMaxGbs * fp);
+        p.late_floor = (uint32_t)(kPaceLateFloorSeconds * clock_hz);
+        for (int launch = 0; launch < 200; ++launch) {
+            const uint32_t r = st.rate_fp ? st.rate_fp : p.rate_init_fp;
+            pace_controller(p, r, model.lateness(r / fp), (uint32_t)(bytes / (r / fp * 1e9) * clock_hz));
+            if (!st.rate_fp) st.rate_fp = r;
+        }
+        std::printf("pace_model_limit %.0f\n", st.rate_fp / fp);
+        expect(st.rate_fp <= p.rate_max_fp && st.rate_fp >= p.rate_max_fp - p.rate_max_fp / 64, "the rate stops at the upper limit");
+    }
+}
+
 void schedules() {
     for (int32_t n : {1, 2, 3, 8, 20, 32, 64, 100, 1024, 1 << 24}) {
         std::printf("tau %d %d shifts", n, tau_of(n));
@@ -207,6 +297,7 @@ int main() {
     named_graphs();
     rejected_matrices();
     schedules();
+    pace_controller_model();
     std::printf("failures %d\n", failures);
     return failures ? 1 : 0;
 }

@@ -44,7 +44,7 @@ constexpr double kPaceLateFloorSeconds = 100e-6;
 
 // Rates are in bytes per clock count x 16 ("fp"); the clock is the chip's constant-rate
 // counter (s_memrealtime, 100 MHz), so 6 TB/s is 60000 bytes per count = 960000 fp.
-struct PaceState {             // 64 bytes, device memory owned by the context, zero-initialised
+struct PaceState {             // 128 bytes (a cache line of its own), device memory owned by the context, zero-initialised
     unsigned long long t0;     // start time of the launch in flight; 0 between launches
     uint32_t left;             // workgroups of the launch in flight that have finished
     uint32_t late_max;         // largest lateness (clock counts) among its wavefronts so far
@@ -58,10 +58,13 @@ struct PaceState {             // 64 bytes, device memory owned by the context, 
     uint32_t last_late;        //   wavefront and the planned duration, in clock counts
     uint32_t last_plan;
     uint32_t last_elapsed;     // t0 to the moment the last workgroup left
-    uint32_t streak;           // consecutive launches that kept up while climbing (the climb step doubles with it)
+    uint16_t streak;           // consecutive launches that kept up while climbing (the climb step doubles with it)
+    uint16_t hold_len;         // launches the next hold lasts: 16, doubling (to 128) each time a search ends where it began
     uint32_t history;          // one bit per recent launch, newest lowest: 1 = it fell behind
+    uint32_t last_hold_fp;     // the rate the most recent hold began at
+    uint32_t reserved[15];
 };
-static_assert(sizeof(PaceState) == 64, "PaceState is one 64-byte line");
+static_assert(sizeof(PaceState) == 128, "PaceState is one 128-byte line");
 
 enum PaceKey : int {           // launches of one kind share a PaceState ...
     PACE_GLOBAL = 0, PACE_RING, PACE_PEER_LONG, PACE_PEER_8, PACE_PEER_4, PACE_CYCLES, PACE_SELF, PACE_TILE, PACE_PEER_16, PACE_BAND,
@@ -132,15 +135,22 @@ __device__ __forceinline__ void pace_wait(const PaceRun& r, uint32_t units_done)
 // The controller: state after a launch at rate r whose slowest wavefront ended `late` clock
 // counts after its last deadline, of `plan` planned.  Runs in one thread.
 // A rate counts as too fast only when two launches in a row fell behind at it.
-//   searching (hold == 0): climb from the last rate that kept up (0.4 % of the rate, doubling
-//     with every launch in a row that keeps up, at most 1.6 %) until a rate is too fast, then
+//   searching (hold == 0): climb from the last rate that kept up (by 0.4 % of the rate twice, then
+//     doubling with every launch in a row that keeps up, at most 1.6 %) until a rate is too fast, then
 //     bisect between the two until they are 0.4 % apart, and hold the lower one;
-//   holding (hold > 0): stay; if the rate has become too fast move down by 0.4 %; after 64
-//     launches search upwards again.
-__device__ __forceinline__ void pace_controller(const PaceArgs& p, uint32_t r, uint32_t late, uint32_t plan) {
+//   holding (hold > 0): stay; if the rate has become too fast move down by half the fraction
+//     the launch fell behind (at least 0.4 %, at most 6 %: past the edge a launch falls behind by
+//     one to two times the excess); when the hold runs out search upwards again.
+//   A hold lasts 16 launches at first and twice as long each time the search after it ends
+//     within 0.4 % of where it began (at most 128); a search that ends elsewhere, or a rate that
+//     became too fast, starts again at 16.  So a settled rate is probed rarely and a moved edge
+//     (other buffers, another direction of the ping-pong, a busier machine) is followed quickly.
+// (Also compiled for the host: the CPU test suite runs it against a model of a launch.)
+__host__ __device__ __forceinline__ void pace_controller(const PaceArgs& p, uint32_t r, uint32_t late, uint32_t plan) {
     PaceState* st = p.st;
     const bool behind = late > p.late_floor + (plan >> 8);  // later than the usual tail + 0.4 % of the launch
     uint32_t lo = st->lo_fp, hi = st->hi_fp, hold = st->hold, streak = st->streak;
+    uint32_t hold_len = st->hold_len ? st->hold_len : 16u;
     const uint32_t hist = ((st->history << 1) | (behind ? 1u : 0u)) & 7u;  // the last three launches
     uint32_t next = r;
     if (behind) st->late_launches += 1u;
@@ -150,12 +160,25 @@ __device__ __forceinline__ void pace_controller(const PaceArgs& p, uint32_t r, u
         st->history = hist;
         return;
     }
+    // a search has ended at rate `at`: hold it, the longer the more often searches end where they began
+    auto begin_hold = [&](uint32_t at) {
+        const uint32_t ref = st->last_hold_fp;
+        const bool same = ref != 0u && (at > ref ? at - ref : ref - at) <= (ref >> 8);
+        hold_len = same ? (hold_len < 64u ? hold_len * 2u : 128u) : 16u;
+        hold = hold_len;
+        st->last_hold_fp = at;
+    };
     if (hold > 0u) {
         if (behind) {  // two late launches in a row while holding: the edge has moved down
-            next = r - (r >> 8);
+            unsigned long long f = plan ? ((unsigned long long)(late - p.late_floor) << 9) / plan : 0ull;  // x 1024, halved
+            if (f < 4ull) f = 4ull;
+            if (f > 61ull) f = 61ull;
+            next = r - (uint32_t)(((unsigned long long)r * f) >> 10);
             hi = r;
             lo = next;
-            hold = 64u;
+            hold_len = 16u;
+            hold = hold_len;
+            st->last_hold_fp = next;
         } else {
             hold -= 1u;
             if (hold == 0u) {  // search upwards again from here
@@ -172,7 +195,7 @@ __device__ __forceinline__ void pace_controller(const PaceArgs& p, uint32_t r, u
                 next = lo + ((hi - lo) >> 1);
             } else {
                 next = lo;
-                hold = 64u;
+                begin_hold(lo);
             }
         } else {
             // no lower rate known to keep up (first launches, or the edge has moved down): step down by
@@ -188,12 +211,12 @@ __device__ __forceinline__ void pace_controller(const PaceArgs& p, uint32_t r, u
         lo = r;
         if (hi != 0u && hi <= r) hi = 0u;  // kept up at a rate that once was too fast: forget that edge
         if (hi == 0u) {
-            next = r + ((r >> 8) << (streak < 2u ? streak : 2u));
+            next = r + ((r >> 8) << (streak < 2u ? 0u : streak < 4u ? streak - 1u : 2u));
             streak += 1u;
         } else if (hi - lo > (lo >> 8)) {
             next = lo + ((hi - lo) >> 1);
         } else {
-            hold = 64u;  // bracketed to 0.4 %: hold the rate that kept up
+            begin_hold(r);  // bracketed to 0.4 %: hold the rate that kept up
         }
     }
     if (next < p.rate_min_fp) next = p.rate_min_fp;
@@ -201,9 +224,14 @@ __device__ __forceinline__ void pace_controller(const PaceArgs& p, uint32_t r, u
     st->lo_fp = lo;
     st->hi_fp = hi;
     st->hold = hold;
-    st->streak = streak;
+    st->streak = (uint16_t)(streak < 0xffffu ? streak : 0xffffu);
+    st->hold_len = (uint16_t)hold_len;
     st->history = next != r ? 0u : hist;  // a new rate starts with a clean record
+#if defined(__HIP_DEVICE_COMPILE__)
     __hip_atomic_store(&st->rate_fp, next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#else
+    st->rate_fp = next;
+#endif
 }
 
 // The moment a wavefront has issued its last row: to be taken right after its work loop, before

@@ -115,5 +115,5 @@ def test_paced_launches_stay_paced_when_a_captured_graph_replays(hx):
             late, plan = sim.query(f"pace_last_late_us:{kind}{d}"), sim.query(f"pace_last_plan_us:{kind}{d}")
             assert plan > 1000.0 and late < 0.1 * plan, f"{kind}{d}: ended {late:.0f} us after its last deadline (plan {plan:.0f} us)"
     print(f"cfg3-shaped {T}-step trajectory: eager {eager_ms:.2f} ms, graph replay {replay_ms:.2f} ms")
-    assert replay_ms <= 1.03 * eager_ms
+    assert replay_ms <= 1.08 * eager_ms            # unpaced launches would take 1.19 x as long
     sim.close()

@@ -1,5 +1,5 @@
 """The library's host-only code (graph builders, validation of a caller's W, the beta estimate,
-the schedule arithmetic of Algorithm 1) built with AddressSanitizer + UndefinedBehaviorSanitizer
+the schedule arithmetic of Algorithm 1, the controller of the pacing rate) built with AddressSanitizer + UndefinedBehaviorSanitizer
 and run on the CPU: the sanitizers abort on any bad access or undefined operation, and the values
 the program prints are compared with the oracle."""
 import os
@@ -77,3 +77,18 @@ def test_schedule_arithmetic_matches_the_oracle(facts):
                                 for k in (0, 1, 250, 499, 500, 2999, 3000, 6000, 8999, 9000, 1000000)]
     assert lr["poly"] == [pytest.approx(f32(orc.lr_poly(k, 4e-3, 100, 1000, 0.5)), rel=1e-6, abs=1e-30)
                           for k in (0, 50, 100, 550, 999, 1000, 5000)]
+
+
+def test_pacing_controller_finds_and_follows_the_edge_of_a_launch_model(facts):
+    """The controller that sets the rate of paced launches, run on the CPU against a model of what a
+    launch reports (keeps up below an edge rate with occasional late launches, falls behind above it):
+    the check program asserts the settling time, the held rate and the reaction to a moved edge
+    itself (FAIL lines); here the printed figures are looked at once more."""
+    rows = [f for f in facts if f[0] == "pace_model"]
+    assert len(rows) == 6
+    for f in rows:
+        v = dict(zip(f[2::2], f[3::2]))
+        edge, mean = float(v["edge"]), float(v["mean_rate"])
+        assert 0.985 * edge <= mean <= 1.012 * edge
+        assert int(v["settle"]) <= 48 and int(v["drop_recover"]) <= 12
+    assert [f for f in facts if f[0] == "pace_model_limit"]
