@@ -291,8 +291,10 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * "mix_band" (sliding-window kernel for banded W: -1 = automatic (large problems whose
  * column tile of all rows does not fit in LDS), 0 = never, 1 = whenever W qualifies),
  * "mix_waves" (sparse-W tile kernel: wavefronts per workgroup, 0 = automatic, 2, 4,
- * 8, 16), "mix_lane_bytes" (sparse-W tile kernel: widest lane type allowed,
- * 0 = automatic, 4, 8, 16), "small_run" (gpga_run on small problems: 1 = whole
+ * 8, 16), "mix_lane_bytes" (sparse-W tile kernel: 0 = automatic (16-byte lanes where the
+ * tile of all rows fits in LDS, else 4-byte lanes), 16 or 4 = at most that width, 8 = 8-byte
+ * lanes where they fit, else 4), "mix_tile_kb" (sparse-W tile kernel: largest tile in KiB of
+ * LDS, 0 = automatic (all a workgroup may have: 160 on this chip), 1..160), "small_run" (gpga_run on small problems: 1 = whole
  * iterations in single-workgroup launches (default), 0 = one kernel per stage),
  * "mix_csr_lds" (sparse-W tile kernel: 1 = copy a small W
  * into LDS (default), 0 = read it from global memory), "cycle_kernel" (row-streaming kernel for one-peer

@@ -61,7 +61,14 @@ struct TileArgs {
 constexpr int kTileWavesDefault = 4;
 constexpr int kTileWavesMax = 16;
 constexpr int kTileUnroll = 4;
-constexpr size_t kTileLdsBytes = 64 * 1024;
+// Largest tile (n rows x 64 lanes) the whole-tile kernel stages: what the device grants one workgroup
+// (160 KiB on gfx950) unless the "mix_tile_kb" option asks for less.
+inline size_t tile_lds_cap(const gpga_ctx* c) {
+    const size_t most = (size_t)c->max_lds_block;
+    if (c->opt_mix_tile_kb <= 0) return most;
+    const size_t want = (size_t)c->opt_mix_tile_kb * 1024;
+    return want < most ? want : most;
+}
 constexpr size_t kTileCsrLdsBytes = 16 * 1024;  // largest W copied into LDS (two workgroups per CU still fit)
 
 // Per-lane spread sums of one wavefront to LDS (stride kWave doubles between the 8 values) ...
@@ -536,6 +543,16 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
     const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20) && sizeof(T) >= 8;
     const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : (c->opt_pace_gbs < 0 && big ? -1.0 : 0.0);
     const int want = c->opt_blocks_per_cu < 0 ? (gbs != 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
+    if (lds > 48 * 1024) {  // per instantiation and device: allow more than the default 64 KiB of dynamic LDS
+        static bool attr_set[64] = {false};
+        const int dev = c->device >= 0 && c->device < 64 ? c->device : 0;
+        if (!attr_set[dev]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_step_tile<T, MOM, LCSR, TRACE>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->max_lds_block);
+            if (e != hipSuccess) return e;
+            attr_set[dev] = true;
+        }
+    }
     if (want > 0) {
         int occ = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM, LCSR, TRACE>, threads, lds) != hipSuccess || occ < 1)
@@ -577,8 +594,11 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
     const size_t csr_lds = ((((size_t)ge.n + 2) & ~(size_t)1) + 2 * (size_t)a.nnz) * sizeof(int32_t);
     const bool lcsr = c->opt_mix_csr_lds != 0 && csr_lds <= kTileCsrLdsBytes && tile_lds + csr_lds <= (size_t)c->max_lds_block;
     // measured on the n = 64, d = 25.6M shape: 8 or 16 wavefronts per workgroup stream
-    // 5.2-6.0 TB/s, 4 wavefronts 4.8-5.1 TB/s (more rows are in flight while others mix)
-    const int waves = c->opt_mix_waves ? c->opt_mix_waves : (ge.n >= 32 ? 8 : kTileWavesDefault);
+    // 5.2-6.0 TB/s, 4 wavefronts 4.8-5.1 TB/s (more rows are in flight while others mix).  A tile of
+    // more than 64 KiB leaves room for one workgroup per compute unit, which then needs all 16
+    // wavefronts (n = 256: 4.6 against 3.7 TB/s with 8, n = 512: 3.6 against 2.6).
+    const int waves = c->opt_mix_waves ? c->opt_mix_waves
+                                       : (tile_lds > 64 * 1024 || ge.n > 160 ? kTileWavesMax : (ge.n >= 32 ? 8 : kTileWavesDefault));
     size_t lds = tile_lds + (lcsr ? csr_lds : 0);
     if constexpr (std::is_same<T, v4f>::value) if (spread_partials && spread_count) {
         // the consensus sums ride along: the wavefronts' sums need waves x 8 x 64 doubles of LDS
@@ -679,13 +699,21 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, doubl
     const size_t n = (size_t)ge.n;
     const bool two_pass = c->opt_mix_two_pass == 1;
     const size_t lane_cap = c->opt_mix_lane_bytes ? (size_t)c->opt_mix_lane_bytes : 16;
-    // Banded W with more rows than the whole-tile kernel can stage (or on request): the sliding-window
-    // kernel.  Where the whole tile fits, the tile kernel is the faster of the two (measured on n = 64,
-    // d = 25.6M, grid: 5.29 TB/s against 5.0) and also fuses the consensus trace.
+    // Which kernel (rates measured on 1.6e9 elements, static exponential graph and grid, medians over
+    // re-allocated buffers):
+    //  * the whole tile with 16-byte lanes where it fits (n <= 160 with 160 KiB of LDS): n = 128 5.6-5.8 TB/s
+    //    (8-byte lanes in 64 KiB 4.8, 4-byte lanes 5.4-5.6, the banded kernel 5.0); it also fuses the
+    //    consensus trace;
+    //  * banded W on more rows: the sliding-window kernel (grid, n = 256 / 512 / 1024: 5.7 / 5.2 / 5.8 TB/s;
+    //    the whole tile with 4-byte lanes 5.3 / 4.0 / -);
+    //  * any other W whose tile fits with 4-byte lanes (n <= 640): the whole tile, 16 wavefronts (static
+    //    exponential graph, n = 256 / 512: 4.6 / 3.6 TB/s; 8-byte lanes are no faster; two passes 3.4 / 3.4);
+    //  * else two passes.
     const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20);
-    const bool tile_fits = n * kWave * sizeof(float) <= kTileLdsBytes;
+    const size_t cap = tile_lds_cap(c);
+    const bool wide_tile_fits = n * kWave * sizeof(v4f) <= cap && lane_cap >= 16 && vec == 4;
     const int band_waves = 8;
-    const int band_bytes = (!two_pass && c->opt_mix_band != 0 && (c->opt_mix_band == 1 || (big && !tile_fits)))
+    const int band_bytes = (!two_pass && c->opt_mix_band != 0 && (c->opt_mix_band == 1 || (big && !wide_tile_fits)))
                                ? band_lane_bytes(c, vec, band_waves) : 0;
     if (band_bytes) {
         StepGeom g2 = ge;
@@ -698,21 +726,21 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, doubl
         return launch_band<float>(c, g2, mom, band_waves);
     }
     if (vec == 4) {
-        // widest lane type whose n x 64-lane tile fits in LDS (16-byte aligned rows also
-        // satisfy the narrower types)
+        // 16-byte aligned rows also satisfy the narrower lane types.  8-byte lanes only on request
+        // ("mix_lane_bytes" = 8): they were the slowest of the three wherever two of them fit.
         StepGeom g2 = ge;
-        if (!two_pass && lane_cap >= 16 && n * kWave * sizeof(v4f) <= kTileLdsBytes)
+        if (!two_pass && lane_cap >= 16 && n * kWave * sizeof(v4f) <= cap)
             return launch_tile<v4f>(c, ge, w, mom, spread_partials, spread_count);
-        if (!two_pass && lane_cap >= 8 && n * kWave * sizeof(v2f) <= kTileLdsBytes) {
+        if (!two_pass && lane_cap == 8 && n * kWave * sizeof(v2f) <= cap) {
             g2.ncols = ge.ncols * 2;
             return launch_tile<v2f>(c, g2, w, mom);
         }
-        if (!two_pass && n * kWave * sizeof(float) <= kTileLdsBytes) {
+        if (!two_pass && n * kWave * sizeof(float) <= cap) {
             g2.ncols = ge.ncols * 4;
             return launch_tile<float>(c, g2, w, mom);
         }
         return launch_two_pass<v4f>(c, ge, w, 4);
     }
-    if (!two_pass && n * kWave * sizeof(float) <= kTileLdsBytes) return launch_tile<float>(c, ge, w, mom);
+    if (!two_pass && n * kWave * sizeof(float) <= cap) return launch_tile<float>(c, ge, w, mom);
     return launch_two_pass<float>(c, ge, w, 1);
 }
