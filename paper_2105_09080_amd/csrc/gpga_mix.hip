@@ -558,11 +558,7 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_tile<T, MOM, LCSR, TRACE>, threads, lds) != hipSuccess || occ < 1)
             occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
-        if (resident < blocks) {
-            const int64_t rounds = (a.tiles + resident - 1) / resident;  // whole rounds: see launch_planned
-            const int64_t even = (a.tiles + rounds - 1) / rounds;
-            blocks = (even * 8 >= resident * 7) ? even : resident;
-        }
+        if (resident < blocks) blocks = balanced_blocks(a.tiles, resident);
         pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_TILE, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
     hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR, TRACE>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
@@ -649,11 +645,7 @@ hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds)
         int occ = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_band<T, MOM>, threads, lds) != hipSuccess || occ < 1) occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
-        if (resident < blocks) {
-            const int64_t rounds = (a.tiles + resident - 1) / resident;  // whole rounds, as for the stencil kernels
-            const int64_t even = (a.tiles + rounds - 1) / rounds;
-            blocks = (even * 8 >= resident * 7) ? even : resident;
-        }
+        if (resident < blocks) blocks = balanced_blocks(a.tiles, resident);
         pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_BAND, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
     hipLaunchKernelGGL((k_step_band<T, MOM>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);

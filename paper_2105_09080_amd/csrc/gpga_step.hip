@@ -740,15 +740,7 @@ hipError_t launch_planned(Kernel kernel, LaunchPlan plan, Args a, hipStream_t st
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, threads, 0) != hipSuccess || occ < 1) occ = 1;
         const int bpc = plan.bpc < occ ? plan.bpc : occ;
         const int64_t resident = (int64_t)plan.num_cus * bpc;
-        if (resident < blocks) {
-            // persistent: each workgroup strides over the work items.  A paced launch lasts as long as
-            // its busiest workgroup, so the items are dealt in whole rounds: with 25000 items and 1024
-            // resident workgroups, 1000 workgroups of 25 items each keep the whole launch busy to the end,
-            // where 1024 would leave 600 of them idle during the last of 25 rounds (2.4 % of the time).
-            const int64_t rounds = (plan.work + resident - 1) / resident;
-            const int64_t even = (plan.work + rounds - 1) / rounds;
-            blocks = (even * 8 >= resident * 7) ? even : resident;
-        }
+        if (resident < blocks) blocks = balanced_blocks(plan.work, resident);  // persistent: each workgroup strides over the work items
         // Pacing needs every workgroup of the launch to be resident at once, which
         // holds here: blocks <= CUs x workgroups per CU that fit.
         pace_setup(const_cast<gpga_ctx*>(plan.ctx), plan.pace_gbs, plan.pace_key, (double)blocks * plan.waves, plan.vec * 4, &a.pace);
