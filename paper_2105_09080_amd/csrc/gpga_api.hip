@@ -869,7 +869,7 @@ gpga_status gpga_tune(gpga_ctx* c, int32_t launches) {
     if (c->aga) return fail(c, GPGA_ESTATE, "adaptive averaging is enabled");
     DeviceGuard guard(c->device);
     // only launches large enough to be paced have a rate to find
-    if (!c->pace_states || c->opt_pace_gbs >= 0 || (int64_t)c->n * c->d * 4 < (256ll << 20)) return GPGA_OK;
+    if (!c->pace_states || c->opt_pace_gbs >= 0 || (int64_t)c->n * c->d * 4 < kPaceMinBytes) return GPGA_OK;
     const int64_t k_saved = c->k;
     double* const trace_saved = c->trace;
     c->trace = nullptr;

@@ -540,7 +540,7 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
     // tiles at the same time and later store the same output rows, so the chip alternates between a pure
     // read phase and a pure write phase over a few rows at a time.  Small problems, or pacing switched
     // off: one workgroup per tile.
-    const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20) && sizeof(T) >= 8;
+    const bool big = (int64_t)c->n * c->d * 4 >= kPaceMinBytes && sizeof(T) >= 8;
     const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : (c->opt_pace_gbs < 0 && big ? -1.0 : 0.0);
     const int want = c->opt_blocks_per_cu < 0 ? (gbs != 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
     if (lds > 48 * 1024) {  // per instantiation and device: allow more than the default 64 KiB of dynamic LDS
@@ -629,7 +629,7 @@ hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds)
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
     pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
-    const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20);
+    const bool big = (int64_t)c->n * c->d * 4 >= kPaceMinBytes;
     const double gbs = c->opt_pace_gbs > 0 ? (double)c->opt_pace_gbs : (c->opt_pace_gbs < 0 && big ? -1.0 : 0.0);
     const int want = c->opt_blocks_per_cu < 0 ? (big || gbs != 0.0 ? 32 : 0) : c->opt_blocks_per_cu;
     // per instantiation and device: allow more than the default 64 KiB of dynamic LDS (setting it twice is harmless)
@@ -701,7 +701,7 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, doubl
     //  * any other W whose tile fits with 4-byte lanes (n <= 640): the whole tile, 16 wavefronts (static
     //    exponential graph, n = 256 / 512: 4.6 / 3.6 TB/s; 8-byte lanes are no faster; two passes 3.4 / 3.4);
     //  * else two passes.
-    const bool big = (int64_t)c->n * c->d * 4 >= (256ll << 20);
+    const bool big = (int64_t)c->n * c->d * 4 >= kPaceMinBytes;
     const size_t cap = tile_lds_cap(c);
     const bool wide_tile_fits = n * kWave * sizeof(v4f) <= cap && lane_cap >= 16 && vec == 4;
     const int band_waves = 8;

@@ -819,7 +819,6 @@ constexpr int64_t kPacedWaves = 2048;
 // persistent and paced, at the rate the controller of their kind has found;
 // everything else is a one-shot launch.
 constexpr int kAutoBlocksPerCu = 4;
-constexpr int64_t kPaceMinBytes = 256ll << 20; // below this a launch is latency-bound anyway
 
 LaunchPlan make_plan(const gpga_ctx* c, int64_t work, int waves, int vec, bool walks_rows, int pace_key) {
     LaunchPlan p;
