@@ -68,7 +68,9 @@ def gossip_kernel_name(topology, n):
         return "k_step_walk for cycles longer than 16 rows, k_step_cycles for cycles of 2 .. 16 rows"
     if topology == "full":
         return "k_step_global"
-    return "k_step_tile" if n <= 256 else "k_step_band where W is banded, else k_update_y + k_spmm_rows"
+    if n <= 160:
+        return "k_step_tile"
+    return "k_step_band where W is banded, else k_step_tile up to 640 rows, else the W = I walk + k_spmm_rows"
 
 
 def parse_args():

@@ -54,7 +54,7 @@ struct TileArgs {
     CsrDev w;
     int64_t tiles;  // column tiles; workgroups stride over them
     int32_t nnz;    // entries of W (the LDS copy needs the count)
-    double* spread_partials;  // TRACE kernels: one sum of squared deviations per column tile
+    double* spread_partials;  // TRACE kernels: one sum of squared deviations per workgroup (nullptr: not wanted)
     PaceArgs pace;
 };
 
@@ -71,41 +71,15 @@ inline size_t tile_lds_cap(const gpga_ctx* c) {
 }
 constexpr size_t kTileCsrLdsBytes = 16 * 1024;  // largest W copied into LDS (two workgroups per CU still fit)
 
-// Per-lane spread sums of one wavefront to LDS (stride kWave doubles between the 8 values) ...
-__device__ __forceinline__ void tile_spread_store(const ColumnSpread<v4f>& sp, double* dst) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        dst[(size_t)j * kWave] = sp.s1[j];
-        dst[(size_t)(4 + j) * kWave] = sp.s2[j];
-    }
-}
-__device__ __forceinline__ void tile_spread_store(const ColumnSpread<v2f>&, double*) {}
-__device__ __forceinline__ void tile_spread_store(const ColumnSpread<float>&, double*) {}
-// ... and this lane's four columns finished from the sums of all `waves` wavefronts.
-template <typename T>
-__device__ __forceinline__ double tile_spread_finish(const double* src, int waves, double inv_n) {
-    double r = 0.0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        double s1 = 0.0, s2 = 0.0;
-        for (int w = 0; w < waves; ++w) {
-            s1 += src[((size_t)w * 8 + j) * kWave];
-            s2 += src[((size_t)w * 8 + 4 + j) * kWave];
-        }
-        const double v = s2 - s1 * s1 * inv_n;
-        r += v > 0.0 ? v : 0.0;
-    }
-    return r;
-}
-
 // LCSR: W is copied into LDS behind the tile once per workgroup and phase 2 reads it from
 // there.  Vector memory operations of a wavefront retire in order, so a neighbour list
 // fetched from global memory inside the output loop would make every output row wait for
 // the stores of the rows before it; LDS reads are counted separately and leave the stores
 // streaming.
-// TRACE (16-byte lanes only): the kernel also leaves, per column tile, the sum over its columns
-// of sum_i (x_new[i] - column mean)^2: every wavefront keeps shifted fp64 sums of the rows it
-// stores, the wavefronts' sums meet in LDS once the tile's y is no longer needed.
+// TRACE: the kernel also leaves, per workgroup, the sum over the columns of its tiles of
+// sum_i (x_new[i] - column mean)^2: every wavefront keeps shifted fp64 sums of the rows it
+// stores, the wavefronts' sums meet in LDS once the tile's y is no longer needed, and the
+// workgroup adds up its tiles in the order it takes them.
 template <typename T, int MOM, bool LCSR, bool TRACE>
 __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
@@ -132,6 +106,7 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
     constexpr uint32_t kLoadUnits = MOM ? 4u : 2u;  // 4-byte streams per row in phase 1 (reads + the m store)
     const PaceRun run = pace_begin(a.pace, lane);
     uint32_t units_done = 0;
+    double wg_spread = 0.0;  // TRACE: lane 0 of wavefront 0 adds up the workgroup's tiles
 
     // Workgroups stride over the column tiles (one tile each in the default one-shot launch).
     // A paced launch has exactly the resident workgroups: they then read the same row group
@@ -254,21 +229,21 @@ __global__ void __launch_bounds__(kWave* kTileWavesMax) k_step_tile(const TileAr
         }
         __syncthreads();  // the next tile's phase 1 overwrites the staged y
         if (TRACE) {
-            // the wavefronts' sums meet in LDS ([wave][8][lane] doubles over the y tile, which is
-            // no longer needed); wavefront 0 adds them in wavefront order, finishes the columns
-            // and leaves one partial for the tile
+            // the wavefronts' sums meet in LDS ([wave][2V][lane] doubles over the y tile, which is
+            // no longer needed); wavefront 0 adds them in wavefront order and finishes the columns
             double* __restrict__ sw = reinterpret_cast<double*>(s_raw);
-            tile_spread_store(spread, sw + ((size_t)wave * 8) * kWave + lane);
+            spread.store(sw + ((size_t)wave * 2 * V) * kWave + lane);
             __syncthreads();
             if (wave == 0) {
-                double part = tile_spread_finish<T>(sw + lane, kTileWaves, 1.0 / (double)n);
+                double part = ColumnSpread<T>::finish(sw + lane, kTileWaves, 1.0 / (double)n);
 #pragma unroll
                 for (int off = kWave / 2; off > 0; off >>= 1) part += __shfl_down(part, off, kWave);
-                if (lane == 0) a.spread_partials[tile] = part;
+                wg_spread += part;
             }
             __syncthreads();
         }
     }
+    if (TRACE && a.spread_partials && threadIdx.x == 0) a.spread_partials[blockIdx.x] = wg_spread;
     pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
 }
 
@@ -293,13 +268,17 @@ struct BandArgs {
     int64_t tiles;
     int32_t band;
     int32_t ring_rows;   // 2*band + 2*waves
+    double* spread_partials;  // TRACE kernels: one sum of squared deviations per workgroup (nullptr: not wanted)
     PaceArgs pace;
 };
 
 constexpr int kBandDepth = 4;    // row batches in flight per wavefront, the one being mixed included
 constexpr int kBandTailMax = 8;  // tail output rows per wavefront: 2*band <= kBandTailMax * waves
 
-template <typename T, int MOM>
+// TRACE: as in the tile kernel, every wavefront keeps shifted fp64 sums of the rows it stores (all relative
+// to y of row 0, which is kept aside anyway), they meet in LDS after the tile's last row, and the workgroup
+// leaves the sum over its tiles.
+template <typename T, int MOM, bool TRACE>
 __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
     constexpr int V = sizeof(T) / sizeof(float);
     extern __shared__ __align__(16) unsigned char s_raw[];
@@ -315,6 +294,7 @@ __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
     const PaceRun run = pace_begin(a.pace, lane);
     uint32_t units_done = 0;
     const int nb = (n + NW - 1) / NW;  // batches of NW rows
+    double wg_spread = 0.0;            // TRACE: lane 0 of wavefront 0 adds up the workgroup's tiles
 
     struct Row {
         T xv, mv, gv;
@@ -380,6 +360,7 @@ __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
         // unrolled kBandDepth times, so every index is a constant.
         Row rows[kBandDepth];
         Taps taps[kBandDepth];
+        ColumnSpread<T> spread;
         // HOT: nothing in the batch is conditional (whole tile, whole batches, every wavefront has an output
         // row whose window lies inside the walk).  Only then can the wait for a batch's data leave exactly the
         // younger loads and stores outstanding; a store under a condition makes that count uncertain and the
@@ -427,6 +408,7 @@ __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
                 if (!HOT && row < 2 * band) head[row * kWave + lane] = y;
             }
             __syncthreads();  // rows < (t + 1) * NW are in the ring
+            if (TRACE && !HOT && t == 0) spread.reset(head[lane]);  // y of row 0: no output row precedes this point
             const int i = row - band;  // this wavefront's output row: its window ends at row i + band = row
             if (HOT || (i >= band && row < n)) {
                 const T acc = mix(tp, [&](int dj) -> T {
@@ -436,6 +418,7 @@ __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
                     return ring[slot * kWave + lane];
                 });
                 if (HOT || on) st_stream(xnp + (int64_t)i * ldT, acc);
+                if (TRACE) spread.add(acc);  // lanes without a column hold zeros throughout
             }
             sb += NW;
             if (sb >= RB) sb -= RB;
@@ -490,9 +473,23 @@ __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
                 return k < band ? ring_row(j) : head[j * kWave + lane];
             });
             if (on) st_stream(xnp + (int64_t)i * ldT, acc);
+            if (TRACE) spread.add(acc);
         }
         __syncthreads();  // the next tile overwrites the ring and the kept rows
+        if (TRACE) {      // the wavefronts' sums meet where the ring was
+            double* __restrict__ sw = reinterpret_cast<double*>(s_raw);
+            spread.store(sw + ((size_t)wave * 2 * V) * kWave + lane);
+            __syncthreads();
+            if (wave == 0) {
+                double part = ColumnSpread<T>::finish(sw + lane, NW, 1.0 / (double)n);
+#pragma unroll
+                for (int off = kWave / 2; off > 0; off >>= 1) part += __shfl_down(part, off, kWave);
+                wg_spread += part;
+            }
+            __syncthreads();
+        }
     }
+    if (TRACE && a.spread_partials && threadIdx.x == 0) a.spread_partials[blockIdx.x] = wg_spread;
     pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
 }
 
@@ -530,8 +527,13 @@ __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, 
 }
 
 
+// Fused consensus sums: one partial per workgroup, if the context's partial-sum array (handed in one slot
+// past its start) has room for them; otherwise the kernel keeps its sums to itself and the caller, who finds
+// *spread_count still 0, takes the separate reduction pass.
+inline bool spread_slots_fit(const gpga_ctx* c, int64_t blocks) { return blocks + 1 <= (int64_t)c->partials_cap; }
+
 template <typename T, int MOM, bool LCSR, bool TRACE>
-hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds) {
+hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds, int64_t* spread_count) {
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
     pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
@@ -561,18 +563,25 @@ hipError_t launch_tile_mom(const gpga_ctx* c, TileArgs a, int waves, size_t lds)
         if (resident < blocks) blocks = balanced_blocks(a.tiles, resident);
         pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_TILE, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
+    if (TRACE) {
+        if (spread_count && a.spread_partials && spread_slots_fit(c, blocks)) *spread_count = blocks;
+        else a.spread_partials = nullptr;
+    }
     hipLaunchKernelGGL((k_step_tile<T, MOM, LCSR, TRACE>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
     return hipGetLastError();
 }
 
 template <typename T, bool TRACE>
-hipError_t launch_tile_traced(const gpga_ctx* c, const TileArgs& a, int waves, size_t lds, bool lcsr, int mom) {
+hipError_t launch_tile_traced(const gpga_ctx* c, const TileArgs& a, int waves, size_t lds, bool lcsr, int mom,
+                              int64_t* spread_count) {
     if (lcsr) {
-        if (mom == 2) return launch_tile_mom<T, 2, true, TRACE>(c, a, waves, lds);
-        return mom == 1 ? launch_tile_mom<T, 1, true, TRACE>(c, a, waves, lds) : launch_tile_mom<T, 0, true, TRACE>(c, a, waves, lds);
+        if (mom == 2) return launch_tile_mom<T, 2, true, TRACE>(c, a, waves, lds, spread_count);
+        return mom == 1 ? launch_tile_mom<T, 1, true, TRACE>(c, a, waves, lds, spread_count)
+                        : launch_tile_mom<T, 0, true, TRACE>(c, a, waves, lds, spread_count);
     }
-    if (mom == 2) return launch_tile_mom<T, 2, false, TRACE>(c, a, waves, lds);
-    return mom == 1 ? launch_tile_mom<T, 1, false, TRACE>(c, a, waves, lds) : launch_tile_mom<T, 0, false, TRACE>(c, a, waves, lds);
+    if (mom == 2) return launch_tile_mom<T, 2, false, TRACE>(c, a, waves, lds, spread_count);
+    return mom == 1 ? launch_tile_mom<T, 1, false, TRACE>(c, a, waves, lds, spread_count)
+                    : launch_tile_mom<T, 0, false, TRACE>(c, a, waves, lds, spread_count);
 }
 
 template <typename T>
@@ -596,17 +605,15 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
     const int waves = c->opt_mix_waves ? c->opt_mix_waves
                                        : (tile_lds > 64 * 1024 || ge.n > 160 ? kTileWavesMax : (ge.n >= 32 ? 8 : kTileWavesDefault));
     size_t lds = tile_lds + (lcsr ? csr_lds : 0);
-    if constexpr (std::is_same<T, v4f>::value) if (spread_partials && spread_count) {
-        // the consensus sums ride along: the wavefronts' sums need waves x 8 x 64 doubles of LDS
-        const size_t meet = (size_t)waves * 8 * kWave * sizeof(double);
-        size_t tile_part = tile_lds < meet ? meet : tile_lds;
-        if (tile_part + (lcsr ? csr_lds : 0) <= (size_t)c->max_lds_block && tile_part == tile_lds) {
+    if (spread_partials && spread_count) {
+        // the consensus sums ride along: the wavefronts' sums meet in waves x 2V x 64 doubles of the tile's LDS
+        const size_t meet = (size_t)waves * 2 * (sizeof(T) / sizeof(float)) * kWave * sizeof(double);
+        if (meet <= tile_lds) {
             a.spread_partials = spread_partials;
-            *spread_count = a.tiles;
-            return launch_tile_traced<T, true>(c, a, waves, lds, lcsr, mom);
+            return launch_tile_traced<T, true>(c, a, waves, lds, lcsr, mom, spread_count);
         }
     }
-    return launch_tile_traced<T, false>(c, a, waves, lds, lcsr, mom);
+    return launch_tile_traced<T, false>(c, a, waves, lds, lcsr, mom, nullptr);
 }
 
 template <typename T>
@@ -624,8 +631,8 @@ hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& 
 // Whether the banded kernel can take this W, and with which lane type: the ring of 2*band + 2*waves rows
 // plus the 2*band kept rows must fit in LDS (at least two workgroups per compute unit), the window must
 // not overlap itself (n >= 4*band), and the tail rows must fit the per-wavefront lists.
-template <typename T, int MOM>
-hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds) {
+template <typename T, int MOM, bool TRACE>
+hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds, int64_t* spread_count) {
     const int threads = kWave * waves;
     int64_t blocks = a.tiles;
     pace_setup(nullptr, 0.0, 0, 0.0, 0, &a.pace);
@@ -636,24 +643,36 @@ hipError_t launch_band_mom(const gpga_ctx* c, BandArgs a, int waves, size_t lds)
     static bool attr_set[64] = {false};
     const int dev = c->device >= 0 && c->device < 64 ? c->device : 0;
     if (!attr_set[dev] && lds > 48 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_step_band<T, MOM>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_step_band<T, MOM, TRACE>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->max_lds_block);
         if (e != hipSuccess) return e;
         attr_set[dev] = true;
     }
     if (want > 0) {
         int occ = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_band<T, MOM>, threads, lds) != hipSuccess || occ < 1) occ = 1;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_step_band<T, MOM, TRACE>, threads, lds) != hipSuccess || occ < 1) occ = 1;
         const int64_t resident = (int64_t)c->num_cus * (want < occ ? want : occ);
         if (resident < blocks) blocks = balanced_blocks(a.tiles, resident);
         pace_setup(const_cast<gpga_ctx*>(c), gbs, PACE_BAND, (double)blocks * waves, (int)sizeof(T), &a.pace);
     }
-    hipLaunchKernelGGL((k_step_band<T, MOM>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
+    if (TRACE) {
+        if (spread_count && a.spread_partials && spread_slots_fit(c, blocks)) *spread_count = blocks;
+        else a.spread_partials = nullptr;
+    }
+    hipLaunchKernelGGL((k_step_band<T, MOM, TRACE>), dim3((unsigned)blocks), dim3(threads), lds, c->stream, a);
     return hipGetLastError();
 }
 
+template <typename T, bool TRACE>
+hipError_t launch_band_traced(const gpga_ctx* c, const BandArgs& a, int waves, size_t lds, int mom, int64_t* spread_count) {
+    if (mom == 2) return launch_band_mom<T, 2, TRACE>(c, a, waves, lds, spread_count);
+    return mom == 1 ? launch_band_mom<T, 1, TRACE>(c, a, waves, lds, spread_count)
+                    : launch_band_mom<T, 0, TRACE>(c, a, waves, lds, spread_count);
+}
+
 template <typename T>
-hipError_t launch_band(const gpga_ctx* c, const StepGeom& ge, int mom, int waves) {
+hipError_t launch_band(const gpga_ctx* c, const StepGeom& ge, int mom, int waves, double* spread_partials,
+                       int64_t* spread_count) {
     BandArgs a;
     a.ge = ge;
     a.off = c->csr_off_d;
@@ -662,9 +681,16 @@ hipError_t launch_band(const gpga_ctx* c, const StepGeom& ge, int mom, int waves
     a.tiles = (ge.ncols + kWave - 1) / kWave;
     a.band = c->csr_band;
     a.ring_rows = 2 * c->csr_band + 2 * waves;
+    a.spread_partials = nullptr;
+    if (a.tiles > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const size_t lds = (size_t)(a.ring_rows + 2 * c->csr_band) * kWave * sizeof(T);
-    if (mom == 2) return launch_band_mom<T, 2>(c, a, waves, lds);
-    return mom == 1 ? launch_band_mom<T, 1>(c, a, waves, lds) : launch_band_mom<T, 0>(c, a, waves, lds);
+    if (spread_partials && spread_count) {
+        // the wavefronts' consensus sums meet in waves x 2V x 64 doubles where the ring was
+        const size_t meet = (size_t)waves * 2 * (sizeof(T) / sizeof(float)) * kWave * sizeof(double);
+        a.spread_partials = spread_partials;
+        return launch_band_traced<T, true>(c, a, waves, lds < meet ? meet : lds, mom, spread_count);
+    }
+    return launch_band_traced<T, false>(c, a, waves, lds, mom, nullptr);
 }
 
 // 0 = W does not qualify, else the lane bytes (16, 8 or 4) the banded kernel would run with.
@@ -709,13 +735,13 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, doubl
                                ? band_lane_bytes(c, vec, band_waves) : 0;
     if (band_bytes) {
         StepGeom g2 = ge;
-        if (vec == 4 && band_bytes == 16) return launch_band<v4f>(c, ge, mom, band_waves);
+        if (vec == 4 && band_bytes == 16) return launch_band<v4f>(c, ge, mom, band_waves, spread_partials, spread_count);
         if (vec == 4 && band_bytes == 8) {
             g2.ncols = ge.ncols * 2;
-            return launch_band<v2f>(c, g2, mom, band_waves);
+            return launch_band<v2f>(c, g2, mom, band_waves, spread_partials, spread_count);
         }
         if (vec == 4) g2.ncols = ge.ncols * 4;
-        return launch_band<float>(c, g2, mom, band_waves);
+        return launch_band<float>(c, g2, mom, band_waves, spread_partials, spread_count);
     }
     if (vec == 4) {
         // 16-byte aligned rows also satisfy the narrower lane types.  8-byte lanes only on request
@@ -725,14 +751,14 @@ hipError_t launch_step_csr(const gpga_ctx* c, const StepGeom& ge, int vec, doubl
             return launch_tile<v4f>(c, ge, w, mom, spread_partials, spread_count);
         if (!two_pass && lane_cap == 8 && n * kWave * sizeof(v2f) <= cap) {
             g2.ncols = ge.ncols * 2;
-            return launch_tile<v2f>(c, g2, w, mom);
+            return launch_tile<v2f>(c, g2, w, mom, spread_partials, spread_count);
         }
         if (!two_pass && n * kWave * sizeof(float) <= cap) {
             g2.ncols = ge.ncols * 4;
-            return launch_tile<float>(c, g2, w, mom);
+            return launch_tile<float>(c, g2, w, mom, spread_partials, spread_count);
         }
         return launch_two_pass<v4f>(c, ge, w, 4);
     }
-    if (!two_pass && n * kWave * sizeof(float) <= cap) return launch_tile<float>(c, ge, w, mom);
+    if (!two_pass && n * kWave * sizeof(float) <= cap) return launch_tile<float>(c, ge, w, mom, spread_partials, spread_count);
     return launch_two_pass<float>(c, ge, w, 1);
 }

@@ -42,8 +42,16 @@ CASES = [
     (64, 100_000, "grid", 0, 0.0, 3, {"mix_waves": 16}),      # 16 wavefronts' sums fill the whole tile
     (32, 100_000, "expo", 0, 0.9, 3, {"mix_waves": 16}),      # ... and do not fit here: reduction pass
     (12, 2000, "expo", 0, 0.9, 4, {}),                        # tile smaller than the sums: reduction pass
-    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8}),  # narrow lanes: reduction pass
-    (300, 2000, "grid", 5, 0.9, 6, {}),                       # two-pass sparse W: reduction pass
+    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8}),  # narrow lanes, more workgroups than partial slots: reduction pass
+    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8, "blocks_per_cu": 2}),   # ... persistent: sums ride along
+    (200, 40_000, "expo", 5, 0.9, 5, {"blocks_per_cu": 1}),   # 4-byte lanes (tile of 200 rows), sums ride along
+    (300, 2000, "grid", 5, 0.9, 6, {}),                       # small problem, 4-byte lanes, one workgroup per tile
+    (300, 2000, "grid", 5, 0.9, 6, {"mix_two_pass": 1}),      # two-pass sparse W: reduction pass
+    (128, 60_000, "grid", 4, 0.9, 6, {"mix_band": 1}),        # sliding-window kernel, 16-byte lanes: sums ride along
+    (128, 60_000, "grid", 0, 0.9, 4, {"mix_band": 1, "mix_lane_bytes": 8, "blocks_per_cu": 1}),
+    (128, 60_000, "grid", 0, 0.0, 4, {"mix_band": 1, "mix_lane_bytes": 4, "blocks_per_cu": 1}),
+    (128, 60_000, "grid", 0, 0.9, 3, {"mix_band": 1, "mix_lane_bytes": 4}),         # more workgroups than slots: reduction pass
+    (36, 30_000, "ring", 3, 0.9, 5, {"mix_band": 1}),         # (the ring stencil kernel; mix_band only matters for sparse W)
     (12, 500, "none", 3, 0.5, 5, {}),
 ]
 
