@@ -263,9 +263,10 @@ gpga_status gpga_consensus_error_static(gpga_ctx* ctx, double* out_dev);
  * trace_dev[k] = ||X^(k+1) - 1 xbar^T||_F (a double on the DEVICE, caller-owned,
  * capacity entries); the caller reads the array whenever it likes after
  * synchronising the stream itself.  After a global average the entry is exactly 0.
- * When the fused gossip kernel stores whole columns (ring on large problems) the
- * sums are taken from the values it stores and X is not read again; otherwise
- * one 4 B/element reduction pass follows the step.  NULL detaches. */
+ * When one wavefront or workgroup of the fused gossip kernel stores whole columns (ring
+ * and one-peer steps on large problems, sparse-W steps in the tile and sliding-window
+ * kernels) the sums are taken from the values it stores and X is not read again;
+ * otherwise one 4 B/element reduction pass follows the step.  NULL detaches. */
 gpga_status gpga_set_trace(gpga_ctx* ctx, double* trace_dev, int64_t capacity);
 
 /* xbar = (1/n) sum_i x_i (App. A notation) of the live X into xbar_dev (d floats
