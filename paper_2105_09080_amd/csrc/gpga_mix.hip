@@ -6,19 +6,20 @@
 // weights w_ij (Sec. 3).  Mixing acts along the node axis only, so a column
 // tile of ALL n rows is self-contained:
 //
-//  * fused tile kernel (n*tile bytes fit in 64 KiB of LDS): a workgroup of four
-//    wavefronts owns one column tile (64 lanes x 16 / 8 / 4 bytes).  Phase 1: the
-//    waves share the rows, read x, m, g once (coalesced row segments), store the
-//    new m and put y = x^(k+1/2) into LDS.  Phase 2: each wave produces its share
-//    of output rows as sum_j w_ij y_j from LDS and streams them to x_new.  Every
-//    element of x, m, g is read from HBM once and m, x_new written once (20 B per
-//    element), exactly like the ring / one-peer stencil kernels.
-//  * two-pass path (more rows than LDS can hold): pass 1 is the elementwise local
-//    update (the W = I walk of the stencil kernel), which writes y over the old
-//    iterate x (dead once y exists: that array is the target of the next step);
-//    pass 2 is the sparse product x_new = W y with workgroups ordered so that
-//    all rows of a column tile run together and re-reads of y hit the caches
-//    (28 B per element of HBM traffic when they do).
+//  * fused tile kernel (the n x 64-lane tile fits in the 160 KiB of LDS a workgroup may
+//    have): a workgroup of 8 or 16 wavefronts owns one column tile (64 lanes x 16 or 4
+//    bytes; 8 on request).  Phase 1: the waves share the rows, read x, m, g once
+//    (coalesced row segments), store the new m and put y = x^(k+1/2) into LDS.  Phase 2:
+//    each wave produces its share of output rows as sum_j w_ij y_j from LDS and streams
+//    them to x_new.  Every element of x, m, g is read from HBM once and m, x_new written
+//    once (20 B per element), exactly like the ring / one-peer stencil kernels.
+//  * sliding-window kernel (banded W: every neighbour within a fixed circular distance of
+//    its node; any number of rows): the same traffic with only a window of y in LDS.
+//  * two-pass path (anything else): pass 1 is the elementwise local update (the W = I
+//    walk of the stencil kernel), which writes y over the old iterate x (dead once y
+//    exists: that array is the target of the next step); pass 2 is the sparse product
+//    x_new = W y with workgroups ordered so that all rows of a column tile run together
+//    and re-reads of y hit the caches (28 B per element of HBM traffic when they do).
 #include <type_traits>
 
 #include "gpga_internal.hpp"

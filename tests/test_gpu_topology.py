@@ -58,7 +58,7 @@ CASES = [
     (12, 1030, 2, "expo", 0.9, False, 0, 5),            # scalar path
     (20, 515, 1, "grid", 0.9, True, 16, 3),
     (20, 515, 1, "grid", 0.9, True, 16, 15),            # global average
-    (64, 4100, 0, "grid", 0.9, False, 48, 7),           # 8 x 8, 16-byte lanes, 64 KiB of LDS
+    (64, 4100, 0, "grid", 0.9, False, 48, 7),           # 8 x 8, 16-byte lanes, a 64 KiB tile
     (64, 4100, 0, "expo", 0.9, False, 48, 7),
     (64, 40_000, 0, "expo", 0.0, False, 0, 0),
     (65, 2052, 0, "grid", 0.9, False, 0, 1),            # 8-byte lanes
