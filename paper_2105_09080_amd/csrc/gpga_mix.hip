@@ -61,7 +61,8 @@ struct TileArgs {
 
 constexpr int kTileWavesDefault = 4;
 constexpr int kTileWavesMax = 16;
-constexpr int kTileUnroll = 4;
+constexpr int kTileUnroll = 2;  // rows per wavefront and batch in phase 1: 1, 2, 4 and 8 measure within the spread between
+                                // buffer placements of each other (5.2-5.9 TB/s on n = 64 and 128), 2 most often ahead
 // Largest tile (n rows x 64 lanes) the whole-tile kernel stages: what the device grants one workgroup
 // (160 KiB on gfx950) unless the "mix_tile_kb" option asks for less.
 inline size_t tile_lds_cap(const gpga_ctx* c) {
