@@ -289,6 +289,8 @@ gpga_status gpga_current_x(const gpga_ctx* ctx, float** x_dev_out);
  * must not exceed "waves"), "row_lanes" (global-average kernel: lanes of a
  * wavefront spread over rows: 0 = automatic, 1, 2, 4), "xcd_swizzle" (0/1),
  * "mix_two_pass" (1 = sparse-W gossip steps always take the two-pass path),
+ * "mix_spmm_lanes" (two-pass path, second pass: lanes per column tile, 0 = automatic
+ * (narrower as n grows, so that a tile's rows stay in one L2), 64, 128, 256),
  * "mix_band" (sliding-window kernel for banded W: -1 = automatic (large problems whose
  * column tile of all rows does not fit in LDS), 0 = never, 1 = whenever W qualifies),
  * "mix_waves" (sparse-W tile kernel: wavefronts per workgroup, 0 = automatic, 2, 4,

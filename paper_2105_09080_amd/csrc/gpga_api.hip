@@ -798,6 +798,9 @@ gpga_status gpga_set_option(gpga_ctx* c, const char* name, int64_t value) {
     } else if (!strcmp(name, "xcd_swizzle")) {
         if (value != 0 && value != 1) return fail(c, GPGA_EINVAL, "xcd_swizzle must be 0 or 1");
         c->opt_xcd_swizzle = (int)value;
+    } else if (!strcmp(name, "mix_spmm_lanes")) {
+        if (value != 0 && value != 64 && value != 128 && value != 256) return fail(c, GPGA_EINVAL, "mix_spmm_lanes must be 0, 64, 128 or 256");
+        c->opt_mix_spmm_lanes = (int)value;
     } else if (!strcmp(name, "mix_tile_kb")) {
         if (value < 0 || value > 160) return fail(c, GPGA_EINVAL, "mix_tile_kb must be 0..160");
         c->opt_mix_tile_kb = (int)value;

@@ -90,6 +90,7 @@ struct gpga_ctx {
     int opt_row_lanes = 0;
     int opt_xcd_swizzle = 0;
     int opt_mix_lane_bytes = 0;  // sparse-W tile kernel: widest lane type allowed (0 = automatic, 4, 8, 16)
+    int opt_mix_spmm_lanes = 0;  // two-pass sparse W, pass 2: lanes per column tile (0 = automatic, 64, 128, 256)
     int opt_mix_tile_kb = 0;     // sparse-W tile kernel: largest tile in KiB of LDS (0 = automatic)
     int opt_mix_waves = 0;       // sparse-W tile kernel: wavefronts per workgroup (0 = automatic, 2, 4, 8, 16)
     int opt_mix_two_pass = 0;  // 1 = sparse-W steps always take the two-pass path

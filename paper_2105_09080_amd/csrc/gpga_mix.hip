@@ -495,32 +495,37 @@ __global__ void __launch_bounds__(kWave* 8) k_step_band(const BandArgs a) {
     pace_end(a.pace, run, units_done, lane, pace_now(a.pace));
 }
 
-// Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  One workgroup = one row of one
-// column tile (256 lanes).  Workgroup ids are dealt to the 8 XCDs round-robin, each
-// with its own L2; the id is remapped so that all rows of a tile run on ONE XCD, in
-// row order: the y rows a tile needs are then fetched into that L2 once and re-read
-// from it by the neighbouring rows.
-template <typename T>
+// Two-pass path, pass 2: x_new[i, :] = sum_j w_ij y[j, :].  One workgroup = 256 / LANES consecutive
+// rows of one column tile of LANES lanes.  Workgroup ids are dealt to the 8 XCDs round-robin, each
+// with its own L2; the id is remapped so that all rows of a tile run on ONE XCD, in row order: the
+// y rows a tile needs are then fetched into that L2 once and re-read from it by the neighbouring
+// rows.  That only works while the tile's y (n x LANES x lane bytes) is well below the 4 MiB of an
+// L2, so tiles get narrower as n grows.
+template <typename T, int LANES>
 __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, float* __restrict__ x_new,
                                                    int64_t ld, int64_t col0, int64_t ncols, int32_t n,
                                                    int64_t tiles, const CsrDev w) {
     constexpr int V = sizeof(T) / sizeof(float);
+    constexpr int R = 256 / LANES;                   // rows per workgroup
     const int64_t ldT = ld / V;
     const int64_t bid = blockIdx.x;
+    const int64_t ng = (n + R - 1) / R;              // row groups per tile
     const int64_t full = (tiles >> 3) << 3;          // tiles covered by whole groups of 8
     int64_t tile;
-    int i;
-    if (bid < full * n) {
+    int g;
+    if (bid < full * ng) {
         const int64_t slot = bid >> 3;               // position within this XCD's queue
-        tile = (slot / n) * 8 + (bid & 7);
-        i = (int)(slot % n);
+        tile = (slot / ng) * 8 + (bid & 7);
+        g = (int)(slot % ng);
     } else {                                         // ragged tail: plain order
-        const int64_t r = bid - full * n;
-        tile = full + r / n;
-        i = (int)(r % n);
+        const int64_t r = bid - full * ng;
+        tile = full + r / ng;
+        g = (int)(r % ng);
     }
-    const int64_t col = tile * 256 + threadIdx.x;
-    if (col >= ncols) return;
+    // a row per wavefront or more: the row index is uniform in a wavefront (scalar loads of the neighbour list)
+    const int i = g * R + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / LANES));
+    const int64_t col = tile * LANES + (threadIdx.x % LANES);
+    if (col >= ncols || i >= n) return;
     const T* __restrict__ yb = reinterpret_cast<const T*>(y + col0) + col;
     const int p0 = w.ptr[i], p1 = w.ptr[i + 1];
     T acc = T(0);
@@ -528,6 +533,15 @@ __global__ void __launch_bounds__(256) k_spmm_rows(const float* __restrict__ y, 
     st_stream(reinterpret_cast<T*>(x_new + col0) + col + (int64_t)i * ldT, acc);
 }
 
+template <typename T, int LANES>
+hipError_t launch_spmm(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w) {
+    const int64_t tiles = (ge.ncols + LANES - 1) / LANES;
+    const int64_t ng = ((int64_t)ge.n + 256 / LANES - 1) / (256 / LANES);
+    if (tiles * ng > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((k_spmm_rows<T, LANES>), dim3((unsigned)(tiles * ng)), dim3(256), 0, c->stream, ge.x, ge.x_new,
+                       ge.ld, ge.col0, ge.ncols, ge.n, tiles, w);
+    return hipGetLastError();
+}
 
 // Fused consensus sums: one partial per workgroup, if the context's partial-sum array (handed in one slot
 // past its start) has room for them; otherwise the kernel keeps its sums to itself and the caller, who finds
@@ -623,11 +637,12 @@ hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& 
     // pass 1: the W = I walk of the stencil kernel, storing y = x^(k+1/2) over the old iterate
     hipError_t e = launch_step_walk(c, ge, MODE_INPLACE, 0, vec);
     if (e != hipSuccess) return e;
-    const int64_t tiles = (ge.ncols + 255) / 256;
-    if (tiles * ge.n > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((k_spmm_rows<T>), dim3((unsigned)(tiles * ge.n)), dim3(256), 0, c->stream, ge.x, ge.x_new,
-                       ge.ld, ge.col0, ge.ncols, ge.n, tiles, w);
-    return hipGetLastError();
+    // tile width: y of all rows of a tile should take a fraction of an L2 (4 MiB)
+    const size_t row_bytes = (size_t)ge.n * sizeof(T);
+    const int lanes = c->opt_mix_spmm_lanes ? c->opt_mix_spmm_lanes : (row_bytes * 256 <= (1u << 20) ? 256 : row_bytes * 128 <= (1u << 20) ? 128 : 64);
+    if (lanes == 256) return launch_spmm<T, 256>(c, ge, w);
+    if (lanes == 128) return launch_spmm<T, 128>(c, ge, w);
+    return launch_spmm<T, 64>(c, ge, w);
 }
 
 // Whether the banded kernel can take this W, and with which lane type: the ring of 2*band + 2*waves rows

@@ -36,7 +36,7 @@ D_CHOICES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1000, 1023, 1024, 1025, 4
              100_001, 300_004, 1_000_000]
 OPTION_CHOICES = (("unroll", [1, 2, 4, 8]), ("waves", [1, 2, 4, 8]), ("row_split", [1, 2, 4, 8]), ("row_lanes", [1, 2, 4]),
                   ("xcd_swizzle", [0, 1]), ("blocks_per_cu", [0, 1, 2, 4, 8]), ("pace_gbs", [0, 2000, 6000, 16000]),
-                  ("cycle_kernel", [0, 1]), ("pace_min_cycle", [2, 4, 8, 64]), ("mix_two_pass", [0, 1]), ("mix_band", [-1, 0, 1]), ("mix_tile_kb", [0, 64, 160]),
+                  ("cycle_kernel", [0, 1]), ("pace_min_cycle", [2, 4, 8, 64]), ("mix_two_pass", [0, 1]), ("mix_band", [-1, 0, 1]), ("mix_tile_kb", [0, 64, 160]), ("mix_spmm_lanes", [0, 64, 128, 256]),
                   ("mix_waves", [2, 4, 8, 16]), ("mix_lane_bytes", [4, 8, 16]), ("mix_csr_lds", [0, 1]))
 
 
