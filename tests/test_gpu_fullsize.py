@@ -107,34 +107,34 @@ CFG3_VARIANTS = [
 ]
 
 
-@pytest.mark.parametrize("topology", ["ring", "expo1"])
-def test_cfg3_every_element_of_one_step_per_kernel_variant(hx, topology):
+@pytest.mark.parametrize("topology,k,what", CFG3_VARIANTS, ids=[f"{t}-k{k}" for t, k, _ in CFG3_VARIANTS])
+def test_cfg3_every_element_of_one_step_per_kernel_variant(hx, topology, k, what):
+    # one test per variant: each lasts seconds, so the run never stays silent for long
     c = inputs.CONFIGS["cfg3"]
     n, d = c["n"], c["d"]
     kw = dict(topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"])
     sim = hx.Simulation(n, d, **kw)
     sim.problem_synthetic(c["seed"], c["grad_var"])
-    for j, (topo, k, what) in enumerate(v for v in CFG3_VARIANTS if v[0] == topology):
-        _random_resident_state(sim, 100 + j)
-        sim.set_state(k=k)
-        sim.local_grad()
-        _full_width_lockstep(sim, k, kw, f"cfg3 {topo} k={k} ({what})")
+    _random_resident_state(sim, 100 + k)
+    sim.set_state(k=k)
+    sim.local_grad()
+    _full_width_lockstep(sim, k, kw, f"cfg3 {topology} k={k} ({what})")
     sim.close()
     del sim
     torch.cuda.empty_cache()
 
 
-def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx):
+@pytest.mark.parametrize("k,what", [(1, "paced one-peer walk, offset 2"), (5, "global average")], ids=["k1", "k5"])
+def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx, k, what):
     c = inputs.CONFIGS["cfg4"]
     n, d = c["n"], c["d"]
     kw = dict(topology="expo1", H=c["H"], lr=c["lr"], momentum=c["momentum"])
     sim = hx.Simulation(n, d, **kw)
     sim.problem_synthetic(c["seed"], c["grad_var"])
-    for j, (k, what) in enumerate([(1, "paced one-peer walk, offset 2"), (5, "global average")]):
-        _random_resident_state(sim, 200 + j)
-        sim.set_state(k=k)
-        sim.local_grad()
-        _full_width_lockstep(sim, k, kw, f"cfg4 expo1 k={k} ({what})", chunk=1 << 21)
+    _random_resident_state(sim, 200 + k)
+    sim.set_state(k=k)
+    sim.local_grad()
+    _full_width_lockstep(sim, k, kw, f"cfg4 expo1 k={k} ({what})", chunk=1 << 21)
     sim.close()
     del sim
     torch.cuda.empty_cache()
