@@ -13,6 +13,8 @@
   both graphs: T = 1000 GPU steps with lock-step checks at a sample of steps spread over
   the whole run, and a free-running comparison (with the oracle's own fp32-storage
   against all-float64 distance beside it) over the first 72 steps.
+* the same replica under Gossip-AGA (Algorithm 2): 96 iterations in lock-step, minibatch
+  losses, period decisions and states against the oracle's.
 """
 import math
 from concurrent.futures import ThreadPoolExecutor
@@ -307,4 +309,45 @@ def test_cfg5_replica_stated_step_size_free_running(hx, topology):
             assert err <= max(TOL_FINAL, 16.0 * floor), f"after {k + 1} steps: GPU vs oracle {err:.2e}, oracle floor {floor:.2e}"
     print(f"cfg5 replica {topology} free-running at lr={c['lr']}: (steps, GPU vs oracle, oracle fp32-storage vs float64) "
           + ", ".join(f"({t}, {e:.2e}, {f:.2e})" for t, e, f in report))
+    sim.close()
+
+
+# ------------------------------------------------------------------ adaptive period (Algorithm 2) on the replica
+
+@pytest.mark.parametrize("topology", ["ring", "expo1"])
+def test_cfg5_replica_gossip_aga_lockstep(hx, topology):
+    # Algorithm 2 on n = 1024 nodes with the virtual-feature logistic problem at the stated step size:
+    # every iteration the oracle's Gossip-AGA is put on the GPU's state (X, M; its own counter C,
+    # F_init and H carry over), fed the oracle's gradients and minibatch losses at that state, and
+    # must reach the same period decision and, within 1e-5, the same next state.
+    c = inputs.CONFIGS["cfg5"]
+    r = _replica()
+    n, d, y, idx, feat = r["n"], r["d"], r["y"], r["idx"], r["feat"]
+    T, H_init, K_w, H_max = 96, 4, 24, 32
+    sim = hx.Simulation(n, d, topology=topology, H=0, lr=c["lr"], momentum=c["momentum"])
+    sim.problem_logreg_virtual(c["seed"], y, c["mu_var"])
+    sim.aga_enable(H_init, K_w, H_max)
+    idx_d = sim.upload_batches(idx[:T])
+    ref = orc.GossipAGA(n, d, topology=topology, H_init=H_init, warmup_iters=K_w, H_max=H_max, lr=c["lr"],
+                        momentum=c["momentum"], storage="f32")
+    periods, worst = [], 0.0
+    for k in range(T):
+        loss = sim.local_loss(idx_d[k])
+        sim.local_grad(idx_d[k])
+        Xg, Mg = host(sim.X), host(sim.M)
+        loss_ref = orc.logreg_loss(feat, y, Xg, idx[k])
+        e_loss = np.abs(host(loss) - loss_ref).max() / max(np.abs(loss_ref).max(), 1e-300)
+        assert e_loss <= TOL_STEP, f"minibatch losses at step {k}: {e_loss:.2e}"
+        ref.pga.X, ref.pga.M = Xg.copy(), Mg.copy()
+        ref.step(orc.logreg_grad(feat, y, Xg, idx[k]), loss_ref)
+        sim.aga_step(loss)
+        assert sim.period == ref.H, f"period differs at step {k}: {sim.period} vs {ref.H}"
+        periods.append(sim.period)
+        ex, em = max(rel_errors(host(sim.X), ref.X)), max(rel_errors(host(sim.M), ref.M))
+        worst = max(worst, e_loss, ex, em)
+        assert ex <= TOL_STEP and em <= TOL_STEP, f"lock-step at step {k}: X {ex:.2e} M {em:.2e}"
+        if ref.history and ref.history[-1][0] == k:
+            assert bool((sim.X == sim.X[0:1]).all()), f"rows differ after the global average of step {k}"
+    assert len(ref.history) >= 3 and len(set(periods)) > 1, (ref.history, "the period never adapted")
+    print(f"cfg5 replica Gossip-AGA {topology}: periods {sorted(set(periods))}, averages at {[h[0] for h in ref.history]}, worst {worst:.2e}")
     sim.close()
