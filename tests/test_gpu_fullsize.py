@@ -142,6 +142,25 @@ def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx, k, what):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("topology,k,what", [("ring", 0, "paced ring walk"), ("expo1", 4, "row-streaming kernel, cycles of 4 rows"),
+                                             ("ring", 47, "global average")], ids=["ring-k0", "expo1-k4", "ring-k47"])
+def test_cfg3_every_element_of_one_step_with_nesterov_momentum(hx, topology, k, what):
+    # the Nesterov variants of the kernels (App. F.1 names the optimizer) in the launch configuration of cfg3
+    c = inputs.CONFIGS["cfg3"]
+    n, d = c["n"], c["d"]
+    kw = dict(topology=topology, H=c["H"], lr=c["lr"], momentum=c["momentum"])
+    sim = hx.Simulation(n, d, **kw)
+    sim.set_nesterov(True)
+    sim.problem_synthetic(c["seed"], c["grad_var"])
+    _random_resident_state(sim, 300 + k)
+    sim.set_state(k=k)
+    sim.local_grad()
+    _full_width_lockstep(sim, k, dict(kw, nesterov=True), f"cfg3 {topology} k={k} ({what}, Nesterov)")
+    sim.close()
+    del sim
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ cfg5 at its full shape
 
 def _virtual_rows_f32(c, node, samples, d, chunk=1 << 17):
