@@ -13,6 +13,8 @@
   both graphs: T = 1000 GPU steps with lock-step checks at a sample of steps spread over
   the whole run, and a free-running comparison (with the oracle's own fp32-storage
   against all-float64 distance beside it) over the first 72 steps.
+* the sparse-W kernels (whole tile, sliding window, two passes) in the launch configurations
+  large problems get: every element of one step on 1.0-1.6e9 elements.
 * the same replica under Gossip-AGA (Algorithm 2): 96 iterations in lock-step, minibatch
   losses, period decisions and states against the oracle's.
 """
@@ -54,13 +56,14 @@ def host(t):
 
 # ------------------------------------------------------------------ cfg3 / cfg4: every element of one step
 
-def _full_width_lockstep(sim, k, kw, what, chunk=1 << 20, workers=6):
+def _full_width_lockstep(sim, k, kw, what, chunk=1 << 20, workers=6, clone_x=False):
     """One gpga_step at iteration k from the state the buffers hold, checked on all n x d
-    elements.  x stays in the old ping-pong buffer and g is not written by the step; m is
-    updated in place, so it is cloned on the device first."""
+    elements.  x stays in the old ping-pong buffer (except on the two-pass sparse-W path,
+    which leaves x^(k+1/2) there: clone_x) and g is not written by the step; m is updated
+    in place, so it is cloned on the device first."""
     d = sim.d
     sim.set_state(k=k)
-    X_old, G, M_old = sim.X, sim.G, sim.M.clone()
+    X_old, G, M_old = (sim.X.clone() if clone_x else sim.X), sim.G, sim.M.clone()
     sim.step()
     torch.cuda.synchronize()
     X_new, M_new = sim.X, sim.M
@@ -156,6 +159,35 @@ def test_cfg3_every_element_of_one_step_with_nesterov_momentum(hx, topology, k, 
     sim.set_state(k=k)
     sim.local_grad()
     _full_width_lockstep(sim, k, dict(kw, nesterov=True), f"cfg3 {topology} k={k} ({what}, Nesterov)")
+    sim.close()
+    del sim
+    torch.cuda.empty_cache()
+
+
+SPARSE_AT_SIZE = [
+    (64, 25_600_000, "grid", "whole-tile kernel, 16-byte lanes, paced"),
+    (64, 25_600_000, "expo", "whole-tile kernel, 16-byte lanes, paced"),
+    (128, 12_800_000, "expo", "whole-tile kernel, 128 KiB tile, 16 wavefronts"),
+    (256, 6_400_000, "expo", "whole-tile kernel, 4-byte lanes, 16 wavefronts"),
+    (256, 6_400_000, "grid", "sliding-window kernel, paced"),
+    (1024, 1_000_000, "grid", "sliding-window kernel, 8-byte lanes, paced"),
+    (1024, 1_000_000, "expo", "two passes"),
+]
+
+
+@pytest.mark.parametrize("n,d,topology,what", SPARSE_AT_SIZE, ids=[f"{n}x{d}-{t}" for n, d, t, _ in SPARSE_AT_SIZE])
+def test_sparse_W_every_element_of_one_step_at_full_size(hx, n, d, topology, what):
+    # the sparse-W kernels in the launch configurations large problems get (synthetic gradients)
+    kw = dict(topology=topology, H=0, lr=0.1, momentum=0.9)
+    sim = hx.Simulation(n, d, **kw)
+    sim.problem_synthetic(7, 1e-3)
+    _random_resident_state(sim, 400)
+    sim.set_state(k=0)
+    sim.local_grad()
+    G_before = sim.G[:, ::997].clone()
+    _full_width_lockstep(sim, 0, kw, f"{n} x {d}, {topology} ({what})", chunk=max(1 << 14, (1 << 26) // n),
+                         clone_x=(what == "two passes"))
+    assert torch.equal(sim.G[:, ::997], G_before), "the step wrote to g"
     sim.close()
     del sim
     torch.cuda.empty_cache()
