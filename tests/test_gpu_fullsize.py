@@ -2,7 +2,7 @@
 
 * cfg3 / cfg4 shapes: ONE fused step per kernel variant compared with the oracle on
   EVERY element (all n x d of X and M), in column chunks: the paced ring walk, the
-  paced one-peer walk over long cycles, the row-streaming kernel over cycles of 16, 8,
+  paced one-peer walk over long cycles, the row-streaming kernel over cycles of 16,
   4 and 2 rows and the global average.  The oracle's step needs no random numbers
   (it is advanced from the GPU's own X, M, G), so a chunk is a few BLAS calls.
 * cfg5 at its full shape (n = 1024, d = 10^6, virtual features), H = 8, 2H + 1 steps
