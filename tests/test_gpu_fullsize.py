@@ -3,7 +3,7 @@
 * cfg3 / cfg4 shapes: ONE fused step per kernel variant compared with the oracle on
   EVERY element (all n x d of X and M), in column chunks: the paced ring walk, the
   paced one-peer walk over long cycles, the row-streaming kernel over cycles of 16,
-  4 and 2 rows and the global average.  The oracle's step needs no random numbers
+  8, 4 and 2 rows and the global average.  The oracle's step needs no random numbers
   (it is advanced from the GPU's own X, M, G), so a chunk is a few BLAS calls.
 * cfg5 at its full shape (n = 1024, d = 10^6, virtual features), H = 8, 2H + 1 steps
   per topology, every step in lock-step: complete gradient rows of eight nodes spread
@@ -19,11 +19,13 @@
   losses, period decisions and states against the oracle's.
 """
 import math
+import queue
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
 from scipy.special import expit
+from threadpoolctl import threadpool_limits
 
 from oracle import gpga_oracle as orc
 from paper_2105_09080_amd import inputs
@@ -56,29 +58,70 @@ def host(t):
 
 # ------------------------------------------------------------------ cfg3 / cfg4: every element of one step
 
-def _full_width_lockstep(sim, k, kw, what, chunk=1 << 20, workers=8, clone_x=False):
+_PINNED = {}
+
+
+def _pinned_slots(count, elems):
+    """`count` sets of five page-locked float32 staging buffers of `elems` elements each, kept for the
+    whole test module (copies from the GPU into page-locked memory run several times faster)."""
+    key = (count, elems)
+    if key not in _PINNED:
+        _PINNED.clear()
+        _PINNED[key] = [[torch.empty(elems, dtype=torch.float32, pin_memory=True) for _ in range(5)] for _ in range(count)]
+    return _PINNED[key]
+
+
+def _full_width_lockstep(sim, k, kw, what, workers=12, clone_x=False):
     """One gpga_step at iteration k from the state the buffers hold, checked on all n x d
     elements.  x stays in the old ping-pong buffer (except on the two-pass sparse-W path,
     which leaves x^(k+1/2) there: clone_x) and g is not written by the step; m is updated
     in place, so it is cloned on the device first."""
-    d = sim.d
+    n, d = sim.n, sim.d
     sim.set_state(k=k)
     X_old, G, M_old = (sim.X.clone() if clone_x else sim.X), sim.G, sim.M.clone()
     sim.step()
     torch.cuda.synchronize()
     X_new, M_new = sim.X, sim.M
     assert X_new.data_ptr() != X_old.data_ptr()
+    # Chunks of 16M elements come to the host through page-locked staging buffers (the main thread copies,
+    # a slot is reused once its chunk has been checked); the workers run the oracle on pieces of 1M
+    # elements, small enough to stay in the caches, with one BLAS thread each (a threaded BLAS serialises
+    # the workers on such small products); the errors are put together again relative to the whole chunk.
+    chunk = max(1024, (1 << 24) // n)
+    piece = max(256, (1 << 20) // n)
+    slots = _pinned_slots(workers + 2, n * chunk)
+    free = queue.SimpleQueue()
+    for slot in slots:
+        free.put(slot)
 
-    def check(c0):
-        c1 = min(d, c0 + chunk)
-        Xo, Mo, Gg = host(X_old[:, c0:c1]), host(M_old[:, c0:c1]), host(G[:, c0:c1])
-        X1, M1 = orc.gossip_pga_step(Xo, Mo, Gg, k, **kw)
-        ex = rel_errors(host(X_new[:, c0:c1]), X1)
-        em = rel_errors(host(M_new[:, c0:c1]), M1)
-        return c0, max(ex), max(em)
+    def check(c0, c1, slot):
+        try:
+            Xo, Mo, Gg, Xn, Mn = (b[: n * (c1 - c0)].view(n, c1 - c0).numpy() for b in slot)
+            acc = {"x": [0.0, 0.0, 0.0, 0.0], "m": [0.0, 0.0, 0.0, 0.0]}   # max |diff|, max |ref|, sum diff^2, sum ref^2
+            for s0 in range(0, c1 - c0, piece):
+                sl = slice(s0, s0 + piece)
+                X1, M1 = orc.gossip_pga_step(Xo[:, sl].astype(np.float64), Mo[:, sl].astype(np.float64),
+                                             Gg[:, sl].astype(np.float64), k, **kw)
+                for key, got, ref in (("x", Xn[:, sl], X1), ("m", Mn[:, sl], M1)):
+                    diff = got - ref
+                    a = acc[key]
+                    a[0], a[1] = max(a[0], np.abs(diff).max()), max(a[1], np.abs(ref).max())
+                    a[2] += float(np.vdot(diff, diff))
+                    a[3] += float(np.vdot(ref, ref))
+            err = {key: max(a[0] / max(a[1], 1e-300), math.sqrt(a[2]) / max(math.sqrt(a[3]), 1e-300)) for key, a in acc.items()}
+            return c0, err["x"], err["m"]
+        finally:
+            free.put(slot)
 
-    with ThreadPoolExecutor(workers) as pool:
-        results = list(pool.map(check, range(0, d, chunk)))
+    with threadpool_limits(limits=1), ThreadPoolExecutor(workers) as pool:
+        futures = []
+        for c0 in range(0, d, chunk):
+            c1 = min(d, c0 + chunk)
+            slot = free.get()                       # waits until a staging slot is free
+            for b, t in zip(slot, (X_old, M_old, G, X_new, M_new)):
+                b[: n * (c1 - c0)].view(n, c1 - c0).copy_(t[:, c0:c1])
+            futures.append(pool.submit(check, c0, c1, slot))
+        results = [f.result() for f in futures]
     worst_x = max(r[1] for r in results)
     worst_m = max(r[2] for r in results)
     bad = [r for r in results if r[1] > TOL_STEP or r[2] > TOL_STEP]
@@ -104,7 +147,9 @@ CFG3_VARIANTS = [
     ("ring", 0, "paced ring walk"),
     ("ring", 47, "global average"),
     ("expo1", 0, "paced one-peer walk, offset 1 (one cycle of 64 rows)"),
+    ("expo1", 1, "paced one-peer walk, offset 2 (two cycles of 32 rows)"),
     ("expo1", 2, "row-streaming kernel, offset 4 (cycles of 16 rows)"),
+    ("expo1", 3, "row-streaming kernel, offset 8 (cycles of 8 rows)"),
     ("expo1", 4, "row-streaming kernel, offset 16 (cycles of 4 rows)"),
     ("expo1", 5, "row-streaming kernel, offset 32 (cycles of 2 rows)"),
 ]
@@ -137,7 +182,7 @@ def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx, k, what):
     _random_resident_state(sim, 200 + k)
     sim.set_state(k=k)
     sim.local_grad()
-    _full_width_lockstep(sim, k, kw, f"cfg4 expo1 k={k} ({what})", chunk=1 << 21)
+    _full_width_lockstep(sim, k, kw, f"cfg4 expo1 k={k} ({what})")
     sim.close()
     del sim
     torch.cuda.empty_cache()
@@ -164,8 +209,10 @@ def test_cfg3_every_element_of_one_step_with_nesterov_momentum(hx, topology, k, 
 
 SPARSE_AT_SIZE = [
     (64, 25_600_000, "grid", "whole-tile kernel, 16-byte lanes, paced"),
+    (64, 25_600_000, "expo", "whole-tile kernel, 16-byte lanes, paced"),
     (128, 12_800_000, "expo", "whole-tile kernel, 128 KiB tile, 16 wavefronts"),
     (256, 6_400_000, "expo", "whole-tile kernel, 4-byte lanes, 16 wavefronts"),
+    (256, 6_400_000, "grid", "sliding-window kernel, paced"),
     (1024, 1_000_000, "grid", "sliding-window kernel, 8-byte lanes, paced"),
     (1024, 1_000_000, "expo", "two passes"),
 ]
@@ -181,8 +228,7 @@ def test_sparse_W_every_element_of_one_step_at_full_size(hx, n, d, topology, wha
     sim.set_state(k=0)
     sim.local_grad()
     G_before = sim.G[:, ::997].clone()
-    _full_width_lockstep(sim, 0, kw, f"{n} x {d}, {topology} ({what})", chunk=max(1 << 14, (1 << 26) // n),
-                         clone_x=(what == "two passes"))
+    _full_width_lockstep(sim, 0, kw, f"{n} x {d}, {topology} ({what})", clone_x=(what == "two passes"))
     assert torch.equal(sim.G[:, ::997], G_before), "the step wrote to g"
     sim.close()
     del sim
