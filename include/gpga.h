@@ -328,10 +328,18 @@ gpga_status gpga_tune(gpga_ctx* ctx, int32_t launches);
  *   "pace_<field>:<kind>" and "pace_<field>:<kind>/1"  state of the pacing controller of one kind
  *       of persistent launch, for steps that read the array bound as x (no suffix) or the one
  *       bound as x_new ("/1"): the two directions of the ping-pong have controllers of their own
- *       (kind: global, ring, peer_long, peer_16, peer_8, peer_4, cycles, self, tile; field: rate_gbs =
+ *       (kind: global, ring, peer_long, peer_16, peer_8, peer_4, cycles, self, tile, band; field: rate_gbs =
  *       rate of the next launch, last_rate_gbs, last_late_us = how long after its last
  *       deadline the slowest wavefront of the most recent launch ended, last_plan_us,
  *       last_elapsed_us, launches, late_launches, hold).  Synchronises the stream.
+ *   "step_path"  which kernels the most recent gpga_step / gpga_aga_step / gpga_run iteration ran as
+ *       (the sizes and W decide; every path has the same semantics): 0 none yet, 1 stencil walk
+ *       (ring, one-peer, W = I), 2 row-streaming one-peer kernel (short cycles), 3 global average,
+ *       4 sparse W with the whole column tile in LDS, 5 sparse banded W with a sliding window,
+ *       6 sparse W in two passes, 7 whole iterations in one workgroup (small problems, gpga_run);
+ *   "step_paced" (1 = that launch was a paced persistent launch), "step_lane_bytes" (16, 8 or 4),
+ *   "trace_fused" (1 = the consensus-trace entry of that step came from the step kernel's own
+ *       sums, 0 = a reduction pass followed or no trace is attached).  These four do not synchronise.
  * EINVAL for an unknown name. */
 gpga_status gpga_query(gpga_ctx* ctx, const char* name, double* value_out);
 

@@ -521,6 +521,9 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
     // one vector pass; else one reduction pass over the new X.  Nothing here waits.
     const bool trace = c->trace && c->k < c->trace_cap;
     int64_t spread_count = 0;
+    c->last_path = PATH_NONE;
+    c->last_paced = 0;
+    c->last_trace_fused = 0;
     hipError_t e = hipSuccess;
     for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {
         ge.col0 = pass == 0 ? 0 : nv * 4;
@@ -542,6 +545,7 @@ static gpga_status run_step(gpga_ctx* c, bool global) {
         if (global) {
             e = launch_trace_store(c, c->partials, 0, slot);
         } else if (spread_count > 0) {
+            c->last_trace_fused = 1;
             e = launch_trace_store(c, c->partials + 1, spread_count, slot);
         } else {
             e = launch_consensus_trace(c, slot);  // reduction pass over the live (new) X
@@ -665,6 +669,10 @@ gpga_status gpga_run(gpga_ctx* c, int64_t T, const int32_t* batch_table_dev, int
             for (int32_t t = 0; t < chunk; ++t) lr[t] = scheduled_lr(c, c->k + t);
             const hipError_t e = launch_small_run(c, chunk, batch_table_dev ? batch_table_dev + j * stride : nullptr, B, lr);
             if (e != hipSuccess) return hip_fail(c, e, "small-problem kernel launch");
+            c->last_path = PATH_SMALL_RUN;
+            c->last_paced = 0;
+            c->last_lane_bytes = 4;
+            c->last_trace_fused = c->trace != nullptr;
             if (chunk % 2) {  // the launch left X where `chunk` separate steps would have: swap the roles like they do
                 float* t = c->x;
                 c->x = c->x_new;
@@ -928,7 +936,12 @@ gpga_status gpga_query(gpga_ctx* c, const char* name, double* value_out) {
         else return fail(c, GPGA_EINVAL, "unknown pacing field in '%s'", name);
         return GPGA_OK;
     }
-    return fail(c, GPGA_EINVAL, "unknown query '%s'", name);
+    if (!strcmp(name, "step_path")) *value_out = c->last_path;
+    else if (!strcmp(name, "step_paced")) *value_out = c->last_paced;
+    else if (!strcmp(name, "step_lane_bytes")) *value_out = c->last_lane_bytes;
+    else if (!strcmp(name, "trace_fused")) *value_out = c->last_trace_fused;
+    else return fail(c, GPGA_EINVAL, "unknown query '%s'", name);
+    return GPGA_OK;
 }
 
 const char* gpga_last_error(const gpga_ctx* c) { return c ? c->err : "null context"; }

@@ -47,7 +47,16 @@ struct PaceState;  // gpga_pace.hpp
 // against 4.9: a paced launch ends about 100 us after its plan whatever its length.
 constexpr int64_t kPaceMinBytes = 512ll << 20;
 
+enum StepPath : int { PATH_NONE = 0, PATH_WALK = 1, PATH_CYCLES = 2, PATH_GLOBAL = 3, PATH_TILE = 4, PATH_BAND = 5,
+                      PATH_TWO_PASS = 6, PATH_SMALL_RUN = 7 };
+
 struct gpga_ctx {
+    void note_path(int path, int lane_bytes) const {
+        if (last_path == PATH_NONE) {
+            last_path = path;
+            last_lane_bytes = lane_bytes;
+        }
+    }
     int32_t n = 0;
     int64_t d = 0;
     int32_t topo = 0;
@@ -90,6 +99,11 @@ struct gpga_ctx {
     int opt_row_lanes = 0;
     int opt_xcd_swizzle = 0;
     int opt_mix_lane_bytes = 0;  // sparse-W tile kernel: widest lane type allowed (0 = automatic, 4, 8, 16)
+    // what the most recent step ran as (gpga_query "step_path" ...): written by the launchers
+    mutable int last_path = 0;        // StepPath; the vector pass of a step decides, a scalar tail pass does not overwrite it
+    mutable int last_paced = 0;       // 1 = that launch was paced
+    mutable int last_lane_bytes = 0;  // bytes per lane of that launch (16, 8, 4)
+    int last_trace_fused = 0;         // 1 = the step kernel itself produced the consensus sums of the trace entry
     int opt_mix_spmm_lanes = 0;  // two-pass sparse W, pass 2: lanes per column tile (0 = automatic, 64, 128, 256)
     int opt_mix_tile_kb = 0;     // sparse-W tile kernel: largest tile in KiB of LDS (0 = automatic)
     int opt_mix_waves = 0;       // sparse-W tile kernel: wavefronts per workgroup (0 = automatic, 2, 4, 8, 16)

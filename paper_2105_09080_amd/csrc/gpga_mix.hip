@@ -603,6 +603,7 @@ hipError_t launch_tile_traced(const gpga_ctx* c, const TileArgs& a, int waves, s
 template <typename T>
 hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int mom,
                        double* spread_partials = nullptr, int64_t* spread_count = nullptr) {
+    c->note_path(PATH_TILE, (int)sizeof(T));
     TileArgs a;
     a.ge = ge;
     a.w = w;
@@ -634,6 +635,7 @@ hipError_t launch_tile(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, i
 
 template <typename T>
 hipError_t launch_two_pass(const gpga_ctx* c, const StepGeom& ge, const CsrDev& w, int vec) {
+    c->note_path(PATH_TWO_PASS, (int)sizeof(T));
     // pass 1: the W = I walk of the stencil kernel, storing y = x^(k+1/2) over the old iterate
     hipError_t e = launch_step_walk(c, ge, MODE_INPLACE, 0, vec);
     if (e != hipSuccess) return e;
@@ -690,6 +692,7 @@ hipError_t launch_band_traced(const gpga_ctx* c, const BandArgs& a, int waves, s
 template <typename T>
 hipError_t launch_band(const gpga_ctx* c, const StepGeom& ge, int mom, int waves, double* spread_partials,
                        int64_t* spread_count) {
+    c->note_path(PATH_BAND, (int)sizeof(T));
     BandArgs a;
     a.ge = ge;
     a.off = c->csr_off_d;

@@ -313,4 +313,5 @@ inline void pace_setup(gpga_ctx* c, double gbs, int key, double wavefronts, int 
     p->rate_min_fp = (uint32_t)lo;
     p->rate_max_fp = (uint32_t)(kPaceMaxGbs * fp);
     p->late_floor = (uint32_t)(kPaceLateFloorSeconds * c->clock_hz);
+    c->last_paced = 1;
 }

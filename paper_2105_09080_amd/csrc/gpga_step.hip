@@ -876,9 +876,11 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
             ca.spread_partials = spread_partials;
             plan.blocks_out = spread_count;
         }
+        c->note_path(PATH_CYCLES, 16);
         return launch_cycles(a.L, momk, traced, plan, ca, c->stream);
     }
 
+    c->note_path(PATH_WALK, vec * 4);
     int Q = 1;
     if (mode != MODE_SELF && mode != MODE_INPLACE) {
         if (c->opt_row_split) {
@@ -953,6 +955,7 @@ hipError_t launch_step_walk(const gpga_ctx* c, const StepGeom& ge, int mode, int
 
 hipError_t launch_step_global(const gpga_ctx* c, const StepGeom& ge, int vec) {
     if (ge.ncols <= 0) return hipSuccess;
+    c->note_path(PATH_GLOBAL, vec * 4);
     const int n = ge.n;
     GlobalArgs a;
     a.ge = ge;

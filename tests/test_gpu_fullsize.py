@@ -71,7 +71,7 @@ def _pinned_slots(count, elems):
     return _PINNED[key]
 
 
-def _full_width_lockstep(sim, k, kw, what, workers=12, clone_x=False):
+def _full_width_lockstep(sim, k, kw, what, workers=12, clone_x=False, expect=None):
     """One gpga_step at iteration k from the state the buffers hold, checked on all n x d
     elements.  x stays in the old ping-pong buffer (except on the two-pass sparse-W path,
     which leaves x^(k+1/2) there: clone_x) and g is not written by the step; m is updated
@@ -81,6 +81,9 @@ def _full_width_lockstep(sim, k, kw, what, workers=12, clone_x=False):
     X_old, G, M_old = (sim.X.clone() if clone_x else sim.X), sim.G, sim.M.clone()
     sim.step()
     torch.cuda.synchronize()
+    if expect is not None:   # (step_path, step_paced) as gpga_query reports them: the variant meant is the one that ran
+        took = (int(sim.query("step_path")), int(sim.query("step_paced")))
+        assert took == expect, f"{what}: ran as path {took[0]}, paced {took[1]}; expected {expect}"
     X_new, M_new = sim.X, sim.M
     assert X_new.data_ptr() != X_old.data_ptr()
     # Chunks of 16M elements come to the host through page-locked staging buffers (the main thread copies,
@@ -143,20 +146,20 @@ def _random_resident_state(sim, seed):
 
 
 # (topology, k) -> kernel variant on the n = 64 shapes with H = 48 (one-peer offset 2^(k mod 6))
-CFG3_VARIANTS = [
-    ("ring", 0, "paced ring walk"),
-    ("ring", 47, "global average"),
-    ("expo1", 0, "paced one-peer walk, offset 1 (one cycle of 64 rows)"),
-    ("expo1", 1, "paced one-peer walk, offset 2 (two cycles of 32 rows)"),
-    ("expo1", 2, "row-streaming kernel, offset 4 (cycles of 16 rows)"),
-    ("expo1", 3, "row-streaming kernel, offset 8 (cycles of 8 rows)"),
-    ("expo1", 4, "row-streaming kernel, offset 16 (cycles of 4 rows)"),
-    ("expo1", 5, "row-streaming kernel, offset 32 (cycles of 2 rows)"),
+CFG3_VARIANTS = [   # the last entry: (step_path, step_paced) the step must report (1 walk, 2 row-streaming, 3 global average)
+    ("ring", 0, "paced ring walk", (1, 1)),
+    ("ring", 47, "global average", (3, 1)),
+    ("expo1", 0, "paced one-peer walk, offset 1 (one cycle of 64 rows)", (1, 1)),
+    ("expo1", 1, "paced one-peer walk, offset 2 (two cycles of 32 rows)", (1, 1)),
+    ("expo1", 2, "row-streaming kernel, offset 4 (cycles of 16 rows)", (2, 1)),
+    ("expo1", 3, "row-streaming kernel, offset 8 (cycles of 8 rows)", (2, 1)),
+    ("expo1", 4, "row-streaming kernel, offset 16 (cycles of 4 rows)", (2, 1)),
+    ("expo1", 5, "row-streaming kernel, offset 32 (cycles of 2 rows)", (2, 1)),
 ]
 
 
-@pytest.mark.parametrize("topology,k,what", CFG3_VARIANTS, ids=[f"{t}-k{k}" for t, k, _ in CFG3_VARIANTS])
-def test_cfg3_every_element_of_one_step_per_kernel_variant(hx, topology, k, what):
+@pytest.mark.parametrize("topology,k,what,expect", CFG3_VARIANTS, ids=[f"{t}-k{k}" for t, k, _, _ in CFG3_VARIANTS])
+def test_cfg3_every_element_of_one_step_per_kernel_variant(hx, topology, k, what, expect):
     # one test per variant: each lasts seconds, so the run never stays silent for long
     c = inputs.CONFIGS["cfg3"]
     n, d = c["n"], c["d"]
@@ -166,14 +169,14 @@ def test_cfg3_every_element_of_one_step_per_kernel_variant(hx, topology, k, what
     _random_resident_state(sim, 100 + k)
     sim.set_state(k=k)
     sim.local_grad()
-    _full_width_lockstep(sim, k, kw, f"cfg3 {topology} k={k} ({what})")
+    _full_width_lockstep(sim, k, kw, f"cfg3 {topology} k={k} ({what})", expect=expect)
     sim.close()
     del sim
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("k,what", [(1, "paced one-peer walk, offset 2"), (5, "global average")], ids=["k1", "k5"])
-def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx, k, what):
+@pytest.mark.parametrize("k,what,expect", [(1, "paced one-peer walk, offset 2", (1, 1)), (5, "global average", (3, 1))], ids=["k1", "k5"])
+def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx, k, what, expect):
     c = inputs.CONFIGS["cfg4"]
     n, d = c["n"], c["d"]
     kw = dict(topology="expo1", H=c["H"], lr=c["lr"], momentum=c["momentum"])
@@ -182,15 +185,15 @@ def test_cfg4_every_element_of_a_gossip_and_a_global_step(hx, k, what):
     _random_resident_state(sim, 200 + k)
     sim.set_state(k=k)
     sim.local_grad()
-    _full_width_lockstep(sim, k, kw, f"cfg4 expo1 k={k} ({what})")
+    _full_width_lockstep(sim, k, kw, f"cfg4 expo1 k={k} ({what})", expect=expect)
     sim.close()
     del sim
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("topology,k,what", [("ring", 0, "paced ring walk"), ("expo1", 4, "row-streaming kernel, cycles of 4 rows"),
-                                             ("ring", 47, "global average")], ids=["ring-k0", "expo1-k4", "ring-k47"])
-def test_cfg3_every_element_of_one_step_with_nesterov_momentum(hx, topology, k, what):
+@pytest.mark.parametrize("topology,k,what,expect", [("ring", 0, "paced ring walk", (1, 1)), ("expo1", 4, "row-streaming kernel, cycles of 4 rows", (2, 1)),
+                                                    ("ring", 47, "global average", (3, 1))], ids=["ring-k0", "expo1-k4", "ring-k47"])
+def test_cfg3_every_element_of_one_step_with_nesterov_momentum(hx, topology, k, what, expect):
     # the Nesterov variants of the kernels (App. F.1 names the optimizer) in the launch configuration of cfg3
     c = inputs.CONFIGS["cfg3"]
     n, d = c["n"], c["d"]
@@ -201,25 +204,25 @@ def test_cfg3_every_element_of_one_step_with_nesterov_momentum(hx, topology, k, 
     _random_resident_state(sim, 300 + k)
     sim.set_state(k=k)
     sim.local_grad()
-    _full_width_lockstep(sim, k, dict(kw, nesterov=True), f"cfg3 {topology} k={k} ({what}, Nesterov)")
+    _full_width_lockstep(sim, k, dict(kw, nesterov=True), f"cfg3 {topology} k={k} ({what}, Nesterov)", expect=expect)
     sim.close()
     del sim
     torch.cuda.empty_cache()
 
 
-SPARSE_AT_SIZE = [
-    (64, 25_600_000, "grid", "whole-tile kernel, 16-byte lanes, paced"),
-    (64, 25_600_000, "expo", "whole-tile kernel, 16-byte lanes, paced"),
-    (128, 12_800_000, "expo", "whole-tile kernel, 128 KiB tile, 16 wavefronts"),
-    (256, 6_400_000, "expo", "whole-tile kernel, 4-byte lanes, 16 wavefronts"),
-    (256, 6_400_000, "grid", "sliding-window kernel, paced"),
-    (1024, 1_000_000, "grid", "sliding-window kernel, 8-byte lanes, paced"),
-    (1024, 1_000_000, "expo", "two passes"),
+SPARSE_AT_SIZE = [   # the last entry: (step_path, step_paced): 4 whole tile, 5 sliding window, 6 two passes
+    (64, 25_600_000, "grid", "whole-tile kernel, 16-byte lanes, paced", (4, 1)),
+    (64, 25_600_000, "expo", "whole-tile kernel, 16-byte lanes, paced", (4, 1)),
+    (128, 12_800_000, "expo", "whole-tile kernel, 128 KiB tile, 16 wavefronts", (4, 1)),
+    (256, 6_400_000, "expo", "whole-tile kernel, 4-byte lanes, 16 wavefronts", (4, 0)),
+    (256, 6_400_000, "grid", "sliding-window kernel, paced", (5, 1)),
+    (1024, 1_000_000, "grid", "sliding-window kernel, 8-byte lanes, paced", (5, 1)),
+    (1024, 1_000_000, "expo", "two passes", (6, 0)),
 ]
 
 
-@pytest.mark.parametrize("n,d,topology,what", SPARSE_AT_SIZE, ids=[f"{n}x{d}-{t}" for n, d, t, _ in SPARSE_AT_SIZE])
-def test_sparse_W_every_element_of_one_step_at_full_size(hx, n, d, topology, what):
+@pytest.mark.parametrize("n,d,topology,what,expect", SPARSE_AT_SIZE, ids=[f"{n}x{d}-{t}" for n, d, t, _, _ in SPARSE_AT_SIZE])
+def test_sparse_W_every_element_of_one_step_at_full_size(hx, n, d, topology, what, expect):
     # the sparse-W kernels in the launch configurations large problems get (synthetic gradients)
     kw = dict(topology=topology, H=0, lr=0.1, momentum=0.9)
     sim = hx.Simulation(n, d, **kw)
@@ -228,7 +231,7 @@ def test_sparse_W_every_element_of_one_step_at_full_size(hx, n, d, topology, wha
     sim.set_state(k=0)
     sim.local_grad()
     G_before = sim.G[:, ::997].clone()
-    _full_width_lockstep(sim, 0, kw, f"{n} x {d}, {topology} ({what})", clone_x=(what == "two passes"))
+    _full_width_lockstep(sim, 0, kw, f"{n} x {d}, {topology} ({what})", clone_x=(what == "two passes"), expect=expect)
     assert torch.equal(sim.G[:, ::997], G_before), "the step wrote to g"
     sim.close()
     del sim

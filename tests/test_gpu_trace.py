@@ -23,41 +23,45 @@ def host(t):
     return t.detach().cpu().numpy().astype(np.float64)
 
 
+# expect = (step_path, trace_fused) of the gossip steps as gpga_query reports them, None where the steps of a run
+# differ among themselves (one-peer offsets) or the case is not about the path.  Paths: 1 stencil walk, 2 row-streaming
+# one-peer kernel, 4 whole-tile sparse W, 5 sliding-window sparse W, 6 two passes.
 CASES = [
-    # n, d, topology, H, momentum, T, opts
-    (8, 600_000, "ring", 4, 0.9, 9, {}),                      # one walker per column: sums ride along
-    (64, 300_004, "ring", 6, 0.9, 8, {}),                     # persistent paced launch, fused sums
-    (64, 300_004, "ring", 0, 0.0, 3, {"blocks_per_cu": 0}),   # one-shot launch, fused sums
-    (5, 1000, "ring", 3, 0.9, 7, {}),                         # short cycle, one walker
-    (5, 1000, "expo1", 3, 0.9, 7, {}),                        # n odd: every one-peer offset is one cycle
-    (64, 4100, "ring", 4, 0.9, 6, {}),                        # rows split over wavefronts: reduction pass
-    (64, 300_004, "expo1", 0, 0.9, 7, {}),                    # several cycles: reduction pass
-    (64, 600_000, "expo1", 0, 0.9, 7, {"blocks_per_cu": 2, "pace_gbs": 4000}),   # paced: one walker takes all cycles
-    (64, 600_000, "expo1", 6, 0.9, 8, {"blocks_per_cu": 4, "pace_gbs": 9000, "unroll": 2}),
-    (24, 600_000, "expo1", 0, 0.9, 6, {"blocks_per_cu": 2, "pace_gbs": 4000}),   # n not a power of two
-    (16, 1003, "ring", 5, 0.9, 6, {}),                        # ragged d: scalar tail -> reduction pass
-    (20, 2000, "grid", 4, 0.9, 6, {}),                        # sparse W, tile kernel: sums ride along
-    (64, 300_004, "grid", 6, 0.9, 7, {}),
-    (64, 300_004, "expo", 0, 0.9, 4, {"blocks_per_cu": 2}),   # workgroups striding over several tiles
-    (64, 100_000, "grid", 0, 0.0, 3, {"mix_waves": 16}),      # 16 wavefronts' sums fill the whole tile
-    (32, 100_000, "expo", 0, 0.9, 3, {"mix_waves": 16}),      # ... and do not fit here: reduction pass
-    (12, 2000, "expo", 0, 0.9, 4, {}),                        # tile smaller than the sums: reduction pass
-    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8}),  # narrow lanes, more workgroups than partial slots: reduction pass
-    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8, "blocks_per_cu": 2}),   # ... persistent: sums ride along
-    (200, 40_000, "expo", 5, 0.9, 5, {"blocks_per_cu": 1}),   # 4-byte lanes (tile of 200 rows), sums ride along
-    (300, 2000, "grid", 5, 0.9, 6, {}),                       # small problem, 4-byte lanes, one workgroup per tile
-    (300, 2000, "grid", 5, 0.9, 6, {"mix_two_pass": 1}),      # two-pass sparse W: reduction pass
-    (128, 60_000, "grid", 4, 0.9, 6, {"mix_band": 1}),        # sliding-window kernel, 16-byte lanes: sums ride along
-    (128, 60_000, "grid", 0, 0.9, 4, {"mix_band": 1, "mix_lane_bytes": 8, "blocks_per_cu": 1}),
-    (128, 60_000, "grid", 0, 0.0, 4, {"mix_band": 1, "mix_lane_bytes": 4, "blocks_per_cu": 1}),
-    (128, 60_000, "grid", 0, 0.9, 3, {"mix_band": 1, "mix_lane_bytes": 4}),         # more workgroups than slots: reduction pass
-    (36, 30_000, "ring", 3, 0.9, 5, {"mix_band": 1}),         # (the ring stencil kernel; mix_band only matters for sparse W)
-    (12, 500, "none", 3, 0.5, 5, {}),
+    # n, d, topology, H, momentum, T, opts, expect
+    (8, 600_000, "ring", 4, 0.9, 9, {}, (1, 1)),                      # one walker per column: sums ride along
+    (64, 300_004, "ring", 6, 0.9, 8, {}, (1, 0)),                     # too few column tiles for one walker each: rows split
+    (64, 300_004, "ring", 0, 0.0, 3, {"blocks_per_cu": 0}, (1, 0)),
+    (64, 1_200_000, "ring", 3, 0.9, 4, {"blocks_per_cu": 4, "pace_gbs": 5000}, (1, 1)),   # persistent paced launch, fused sums
+    (5, 1000, "ring", 3, 0.9, 7, {}, (1, 1)),                         # short cycle, one walker
+    (5, 1000, "expo1", 3, 0.9, 7, {}, (1, 1)),                        # n odd: every one-peer offset is one cycle
+    (64, 4100, "ring", 4, 0.9, 6, {}, (1, 0)),                        # rows split over wavefronts: reduction pass
+    (64, 300_004, "expo1", 0, 0.9, 7, {}, None),                      # several cycles: reduction pass
+    (64, 600_000, "expo1", 0, 0.9, 7, {"blocks_per_cu": 2, "pace_gbs": 4000}, None),   # paced: one walker takes all cycles
+    (64, 600_000, "expo1", 6, 0.9, 8, {"blocks_per_cu": 4, "pace_gbs": 9000, "unroll": 2}, None),
+    (24, 600_000, "expo1", 0, 0.9, 6, {"blocks_per_cu": 2, "pace_gbs": 4000}, None),   # n not a power of two
+    (16, 1003, "ring", 5, 0.9, 6, {}, (1, 0)),                        # ragged d: scalar tail -> reduction pass
+    (20, 2000, "grid", 4, 0.9, 6, {}, (4, 1)),                        # sparse W, tile kernel: sums ride along
+    (64, 300_004, "grid", 6, 0.9, 7, {}, (4, 1)),
+    (64, 300_004, "expo", 0, 0.9, 4, {"blocks_per_cu": 2}, (4, 1)),   # workgroups striding over several tiles
+    (64, 100_000, "grid", 0, 0.0, 3, {"mix_waves": 16}, (4, 1)),      # 16 wavefronts' sums fill the whole tile
+    (32, 100_000, "expo", 0, 0.9, 3, {"mix_waves": 16}, (4, 0)),      # ... and do not fit here: reduction pass
+    (12, 2000, "expo", 0, 0.9, 4, {}, (4, 0)),                        # tile smaller than the sums: reduction pass
+    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8}, (4, 0)),  # narrow lanes, more workgroups than partial slots: reduction pass
+    (64, 100_000, "grid", 0, 0.9, 3, {"mix_lane_bytes": 8, "blocks_per_cu": 2}, (4, 1)),   # ... persistent: sums ride along
+    (200, 60_000, "expo", 5, 0.9, 5, {"blocks_per_cu": 1}, (4, 1)),   # 4-byte lanes (tile of 200 rows), sums ride along
+    (300, 2000, "grid", 5, 0.9, 6, {}, (4, 0)),                       # small problem, 4-byte lanes, one workgroup per tile
+    (300, 2000, "grid", 5, 0.9, 6, {"mix_two_pass": 1}, (6, 0)),      # two-pass sparse W: reduction pass
+    (128, 60_000, "grid", 4, 0.9, 6, {"mix_band": 1}, (5, 1)),        # sliding-window kernel, 16-byte lanes: sums ride along
+    (128, 60_000, "grid", 0, 0.9, 4, {"mix_band": 1, "mix_lane_bytes": 8, "blocks_per_cu": 1}, (5, 1)),
+    (128, 60_000, "grid", 0, 0.0, 4, {"mix_band": 1, "mix_lane_bytes": 4, "blocks_per_cu": 1}, (5, 1)),
+    (128, 60_000, "grid", 0, 0.9, 3, {"mix_band": 1, "mix_lane_bytes": 4}, (5, 0)),   # more workgroups than slots: reduction pass
+    (36, 30_000, "ring", 3, 0.9, 5, {"mix_band": 1}, None),           # (the ring stencil kernel; mix_band only matters for sparse W)
+    (12, 500, "none", 3, 0.5, 5, {}, None),
 ]
 
 
-@pytest.mark.parametrize("n,d,topology,H,momentum,T,opts", CASES)
-def test_trace_matches_the_oracles_consensus_distance(hx, n, d, topology, H, momentum, T, opts):
+@pytest.mark.parametrize("n,d,topology,H,momentum,T,opts,expect", CASES)
+def test_trace_matches_the_oracles_consensus_distance(hx, n, d, topology, H, momentum, T, opts, expect):
     sim = hx.Simulation(n, d, topology=topology, H=H, lr=0.05, momentum=momentum)
     for name, v in opts.items():
         sim.set_option(name, v)
@@ -68,6 +72,9 @@ def test_trace_matches_the_oracles_consensus_distance(hx, n, d, topology, H, mom
         sim.local_grad()
         X_prev, M_prev, G_prev = host(sim.X), (host(sim.M) if momentum else None), host(sim.G)
         sim.step()
+        if expect is not None and not orc.is_global_step(k, H):
+            took = (int(sim.query("step_path")), int(sim.query("trace_fused")))
+            assert took == expect, f"step {k} ran as path {took[0]} with trace_fused {took[1]}, expected {expect}"
         X = host(sim.X)
         # the traced launches are also ordinary steps: one oracle step from the GPU's previous state
         X1, _ = orc.gossip_pga_step(X_prev, M_prev if momentum else np.zeros_like(X_prev), G_prev, k,
