@@ -100,6 +100,7 @@ def test_trajectory_matches_the_oracle_driver(hx, kind, n, d, M, B, topology, H,
     bufs = [b.data_ptr() for b in sim._bufs]
     x_before = sim.X.data_ptr()
     sim.run(T, sim.upload_batches(idx) if B else None)
+    assert int(sim.query("step_path")) == 7, "gpga_run did not take the single-workgroup path on this problem"
     # the live X sits where T separate steps would leave it: the roles of x / x_new swap once per iteration
     assert sim.k == k0 + T and sim.X.data_ptr() == bufs[(bufs.index(x_before) + T) % 2]
     ref = orc.GossipPGA(n, d, topology=topology, H=H, lr=LR, momentum=momentum, nesterov=nesterov, x0=x0,
@@ -198,6 +199,7 @@ def test_iteration_rate_on_the_simulation_shape(hx):
         sim.run(T, idx_d)
         torch.cuda.synchronize()
         rates[small] = T / (time.perf_counter() - t0)
+        assert (int(sim.query("step_path")) == 7) == small
         sim.close()
     # a figure for the record, not an assertion: wall-clock comparisons do not belong in a parity suite
     print(f"iterations/s: single-workgroup path {rates[True]:.0f}, kernel-per-stage path {rates[False]:.0f}")

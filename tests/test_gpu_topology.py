@@ -109,6 +109,7 @@ def test_two_pass_path_gives_the_tile_kernels_answer_and_leaves_g_alone(hx, n, d
         sim.set_option("mix_two_pass", two_pass)
         sim.set_state(X=X, M=Mb, G=G, k=0)
         sim.step()
+        assert int(sim.query("step_path")) == (6 if two_pass else 4)
         outs.append((host(sim.X), host(sim.M), host(sim.G)))
         sim.close()
     X_ref, M_ref = orc.gossip_pga_step(X, Mb, G, 0, topology=topology, H=0, lr=0.1, momentum=0.9)
@@ -230,7 +231,8 @@ BAND_CASES = [
     (100, 2052, 0, "grid", 0.9, True),           # 10 x 10
     (256, 1000, 0, "grid", 0.9, False),          # 16 x 16
     (1024, 2052, 0, "grid", 0.9, False),         # 32 x 32: band 32, the kept rows and the ring hold 144 rows
-    (1023, 700, 0, "grid", 0.5, False),          # 31 x 33: n not a multiple of the wavefronts per workgroup
+    (1023, 700, 0, 31, 0.5, False),              # n not a multiple of the wavefronts per workgroup
+    (992, 516, 0, "grid", 0.9, False),           # 31 x 32
     (37, 900, 0, 1, 0.9, False),                 # a ring with random weights
     (50, 1234, 0, 3, 0.9, False),
     (333, 640, 0, 7, 0.9, True),
@@ -254,6 +256,7 @@ def test_banded_W_sliding_window_kernel_matches_oracle(hx, n, d, pad, topology, 
     sim.set_state(X=X, M=Mb, G=G, k=0)
     for k in range(2):          # two steps: both directions of the ping-pong
         sim.step()
+        assert int(sim.query("step_path")) == 5, "the sliding-window kernel did not take this W"
         X_ref, M_ref = orc.gossip_pga_step(X_ref, M_ref, G, k, topology=name, H=0, lr=lr, momentum=momentum,
                                            nesterov=nesterov, W=W)
         X_ref = X_ref.astype(np.float32).astype(np.float64)
@@ -262,6 +265,20 @@ def test_banded_W_sliding_window_kernel_matches_oracle(hx, n, d, pad, topology, 
         if momentum:
             assert_close(host(sim.M), M_ref, TOL_STEP, f"M after step {k}")
     np.testing.assert_array_equal(host(sim.G), G.astype(np.float64))      # the gradients are only read
+    sim.close()
+
+
+def test_a_band_wider_than_the_kernel_takes_falls_back_to_two_passes(hx):
+    n, d = 1023, 700             # 31 x 33 torus: neighbours 33 rows away, one more than the sliding window holds
+    X, Mb, G = inputs.random_state(n, d, seed=5)
+    sim = hx.Simulation(n, d, topology="grid", H=0, lr=0.1, momentum=0.5)
+    sim.set_option("mix_band", 1)
+    sim.set_state(X=X, M=Mb, G=G, k=0)
+    sim.step()
+    assert int(sim.query("step_path")) == 6
+    X_ref, M_ref = orc.gossip_pga_step(X, Mb, G, 0, topology="grid", H=0, lr=0.1, momentum=0.5)
+    assert_close(host(sim.X), X_ref, TOL_STEP, "X")
+    assert_close(host(sim.M), M_ref, TOL_STEP, "M")
     sim.close()
 
 
@@ -277,6 +294,9 @@ def test_banded_kernel_persistent_and_paced(hx, opts):
         sim.set_option(name, v)
     sim.set_state(X=X, M=Mb, G=G, k=0)
     sim.step()
+    assert int(sim.query("step_path")) == 5
+    assert int(sim.query("step_paced")) == (1 if "pace_gbs" in opts else 0)
+    assert int(sim.query("step_lane_bytes")) == opts.get("mix_lane_bytes", 16)
     X_ref, M_ref = orc.gossip_pga_step(X, Mb, G, 0, topology="grid", H=0, lr=0.1, momentum=0.9)
     assert_close(host(sim.X), X_ref, TOL_STEP, "X")
     assert_close(host(sim.M), M_ref, TOL_STEP, "M")
