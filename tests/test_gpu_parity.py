@@ -130,8 +130,8 @@ def test_every_launch_geometry_gives_the_same_answer(hx, opts, n, d, topology):
 
 @pytest.mark.parametrize("topology,k,H", [("ring", 0, 0), ("expo1", 0, 0), ("expo1", 3, 0), ("expo1", 5, 0),
                                           ("ring", 5, 6), ("none", 1, 0)])
-@pytest.mark.parametrize("opts", [{"blocks_per_cu": 1, "waves": 1, "pace_gbs": 2000},
-                                  {"blocks_per_cu": 2, "waves": 2, "pace_gbs": 8000, "unroll": 4},
+@pytest.mark.parametrize("opts", [{"blocks_per_cu": 1, "waves": 1, "pace_gbs": 2000, "pace_min_cycle": 2},
+                                  {"blocks_per_cu": 2, "waves": 2, "pace_gbs": 8000, "unroll": 4, "row_split": 1, "pace_min_cycle": 2},
                                   {"blocks_per_cu": 1, "waves": 4, "pace_gbs": 0, "unroll": 1}],
                          ids=["paced-w1", "paced-w2-u4", "persistent-unpaced"])
 def test_persistent_paced_launch_matches_oracle(hx, topology, k, H, opts):
@@ -144,8 +144,13 @@ def test_persistent_paced_launch_matches_oracle(hx, topology, k, H, opts):
         sim.set_option(name, v)
     X_ref, M_ref = X, Mb
     sim.set_state(X=X, M=Mb, G=G, k=k)
-    for j in range(3):          # several launches in a row reuse / recycle the start-time slots
+    for j in range(3):          # several launches in a row share one pacing state
         sim.step()
+        # (the W = I step is never paced: its one-shot launch keeps a single row open per workgroup anyway; the
+        # global average at this width spreads rows over lanes and wavefronts, which is not paced either: its
+        # paced form is checked at full size)
+        want_paced = opts["pace_gbs"] and topology != "none" and not orc.is_global_step(k + j, H)
+        assert int(sim.query("step_paced")) == (1 if want_paced else 0), f"step {j}: pacing is not as asked for"
         X_ref, M_ref = orc.gossip_pga_step(X_ref, M_ref, G, k + j, topology=topology, H=H, lr=0.1, momentum=0.9)
         X_ref = X_ref.astype(np.float32).astype(np.float64)
         M_ref = M_ref.astype(np.float32).astype(np.float64)
@@ -176,6 +181,8 @@ def test_whole_cycle_kernel_for_short_one_peer_cycles(hx, n, d, k, momentum, opt
             sim.set_option(name, v)
         sim.set_state(X=X, M=Mb, G=G, k=k)
         sim.step()
+        # the row-streaming kernel takes the 16-byte columns of cycles of 2, 4, 8 or 16 rows unless switched off
+        assert int(sim.query("step_path")) == (2 if opts["cycle_kernel"] and d % 4 == 0 else 1)
         X_ref, M_ref = orc.gossip_pga_step(X, Mb if momentum else np.zeros_like(Mb), G, k, topology="expo1", H=0,
                                            lr=0.1, momentum=momentum, nesterov=nesterov)
         assert_close(host(sim.X), X_ref, TOL_STEP, "X")
