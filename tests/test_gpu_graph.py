@@ -22,7 +22,8 @@ def hx():
 @pytest.mark.parametrize("n,d,topology,opts", [
     (8, 1000, "ring", {}),
     (20, 515, "grid", {}),
-    (64, 300_004, "expo1", {"blocks_per_cu": 2, "pace_gbs": 4000}),   # paced persistent launches inside the graph
+    # paced persistent launches inside the graph (one walker per cycle and short cycles paced too, so that every gossip step is)
+    (64, 300_004, "expo1", {"blocks_per_cu": 2, "pace_gbs": 4000, "row_split": 1, "pace_min_cycle": 2}),
 ])
 def test_captured_trajectory_replays_to_the_eager_result(hx, n, d, topology, opts):
     M, Bsz, T, H = 30, 4, 12, 4                       # T even: x / x_new end in the roles they started in
@@ -62,6 +63,10 @@ def test_captured_trajectory_replays_to_the_eager_result(hx, n, d, topology, opt
             assert torch.equal(sim._bufs[0][:, :d], X_eager), rep
             assert torch.equal(sim.M, M_eager), rep
             assert torch.equal(trace, tr_eager), rep
+    if "pace_gbs" in opts:   # the eager run and the three replays: every gossip step was a paced launch each time
+        kinds = ("peer_long", "peer_16", "peer_8", "peer_4", "cycles")
+        paced = sum(sim.query(f"pace_launches:{k}{dr}") for k in kinds for dr in ("", "/1"))
+        assert paced == 4 * sum(1 for k in range(T) if (k + 1) % H), paced
     sim.close()
 
 
