@@ -52,8 +52,8 @@ NESTEROV_CASES = [
     (1024, 520, 0, "expo1", 0.9, 0, 3),
     (16, 777, 0, "none", 0.9, 5, 1),
     (16, 777, 0, "full", 0.3, 0, 1),
-    (64, 300_004, 0, "ring", 0.9, 0, 0),      # persistent launch
-    (64, 300_004, 0, "expo1", 0.9, 6, 5),     # persistent global average
+    (64, 300_004, 0, "ring", 0.9, 0, 0),      # wide rows: several column tiles per workgroup
+    (64, 300_004, 0, "expo1", 0.9, 6, 5),     # ... and the global average on them
 ]
 
 
@@ -74,6 +74,29 @@ def test_nesterov_step_matches_oracle(hx, n, d, pad, topology, momentum, H, k):
     if orc.is_global_step(k, H) or topology == "full":
         Xg = sim.X.cpu().numpy()
         assert all(np.array_equal(Xg[0], Xg[i]) for i in range(n))
+    sim.close()
+
+
+@pytest.mark.parametrize("topology,k,path", [("ring", 0, 1), ("expo1", 0, 1), ("expo1", 4, 2)])
+def test_nesterov_step_in_paced_persistent_launches(hx, topology, k, path):
+    # the Nesterov variants of the walk and of the row-streaming kernel as paced persistent launches
+    # (forced by options at a size the oracle handles whole; the default launches of large problems are
+    # checked at full size)
+    n, d = 64, 300_004
+    X, Mb, G = inputs.random_state(n, d, seed=4100 + k)
+    sim = hx.Simulation(n, d, topology=topology, H=0, lr=0.37, momentum=0.9)
+    sim.set_nesterov(True)
+    opts = {"blocks_per_cu": 2, "pace_gbs": 5000, "cycle_kernel": 1}
+    if path == 1:
+        opts["row_split"] = 1          # one walker per cycle (the row-streaming kernel never splits rows)
+    for name, v in opts.items():
+        sim.set_option(name, v)
+    sim.set_state(X=X, M=Mb, G=G, k=k)
+    sim.step()
+    assert (int(sim.query("step_path")), int(sim.query("step_paced"))) == (path, 1)
+    X_ref, M_ref = orc.gossip_pga_step(X, Mb, G, k, topology=topology, H=0, lr=0.37, momentum=0.9, nesterov=True)
+    assert_close(host(sim.X), X_ref, TOL_STEP, "X")
+    assert_close(host(sim.M), M_ref, TOL_STEP, "M")
     sim.close()
 
 
