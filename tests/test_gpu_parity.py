@@ -405,7 +405,7 @@ def _work_item_slabs(d, width=1024, resident=1024):
     return np.unique(cols)
 
 
-def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None, nesterov=False, H=None):
+def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None, nesterov=False, H=None, gossip_path=None):
     """Column-separable workloads (synthetic gradients): the GPU runs the full array, the
     oracle follows column slabs (evenly spaced ones plus slabs placed on the first and last
     tile groups of several work items of the persistent launch).  Every step is checked in
@@ -435,6 +435,8 @@ def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None, 
         assert_close(Gs, G_ref, TOL_STEP, f"G at step {k}")
         X1, M1 = orc.gossip_pga_step(Xs, Ms, Gs, k, **kw)
         sim.step()
+        if gossip_path is not None and not orc.is_global_step(k, H if H is not None else c["H"]):
+            assert int(sim.query("step_path")) in gossip_path, f"step {k} ran as path {int(sim.query('step_path'))}"
         ref.step(G_ref)
         Xn = slab(sim.X)
         for got, want, what in ((Xn, X1, "X"), (slab(sim.M), M1, "M")):
@@ -462,29 +464,32 @@ def _slab_trajectory(hx, cfg_name, topology, n_slabs, width, T=None, opts=None, 
 
 @pytest.mark.parametrize("topology", ["ring", "expo1"])
 def test_cfg3_resnet50_sized_slabs(hx, topology):
-    _slab_trajectory(hx, "cfg3", topology, n_slabs=32, width=1024)
+    _slab_trajectory(hx, "cfg3", topology, n_slabs=32, width=1024, gossip_path=(1, 2))    # stencil walk / row-streaming kernel
 
 
 @pytest.mark.parametrize("topology,nesterov", [("grid", False), ("expo", True), ("ring", True)])
 def test_cfg3_sized_slabs_sparse_W_and_nesterov(hx, topology, nesterov):
     # the widened variants at the benchmark's full size: LDS-tile kernel (grid, static exponential
     # graph) and Nesterov momentum, two averaging periods
-    _slab_trajectory(hx, "cfg3", topology, n_slabs=32, width=1024, T=17, nesterov=nesterov, H=8)
+    _slab_trajectory(hx, "cfg3", topology, n_slabs=32, width=1024, T=17, nesterov=nesterov, H=8,
+                     gossip_path=(1,) if topology == "ring" else (4,))
 
 
-def test_cfg5_sized_slabs_sparse_W_two_pass(hx):
-    # n = 1024 rows: update pass writing y over g, then the sparse product (synthetic gradients
-    # on the cfg5 shape so that the oracle can follow column slabs)
+@pytest.mark.parametrize("topology,path", [("grid", 5), ("expo", 6)])
+def test_cfg5_sized_slabs_sparse_W(hx, topology, path):
+    # n = 1024 rows (synthetic gradients on the cfg5 shape so that the oracle can follow column slabs): the
+    # 32 x 32 grid is banded and takes the sliding-window kernel, the static exponential graph the two passes
+    # (local update written over the old iterate, then the sparse product)
     c = dict(inputs.CONFIGS["cfg5"], problem="synthetic", grad_var=1e-3)
     inputs.CONFIGS["cfg5_synth"] = c
     try:
-        _slab_trajectory(hx, "cfg5_synth", "grid", n_slabs=16, width=256, T=10, H=8)
+        _slab_trajectory(hx, "cfg5_synth", topology, n_slabs=16, width=256, T=10, H=8, gossip_path=(path,))
     finally:
         del inputs.CONFIGS["cfg5_synth"]
 
 
 def test_cfg4_bert_base_sized_slabs(hx):
-    _slab_trajectory(hx, "cfg4", "expo1", n_slabs=32, width=1024)
+    _slab_trajectory(hx, "cfg4", "expo1", n_slabs=32, width=1024, gossip_path=(1, 2))
 
 
 _REPLICA = {}
