@@ -60,17 +60,9 @@ PAPER_CONTEXT = {
 }
 
 
-def gossip_kernel_name(topology, n):
-    """Which fused kernels run the gossip steps of this workload."""
-    if topology in ("ring", "none"):
-        return "k_step_walk"
-    if topology == "expo1":
-        return "k_step_walk for cycles longer than 16 rows, k_step_cycles for cycles of 2 .. 16 rows"
-    if topology == "full":
-        return "k_step_global"
-    if n <= 160:
-        return "k_step_tile"
-    return "k_step_band where W is banded, else k_step_tile up to 640 rows, else the W = I walk + k_spmm_rows"
+# gpga_query "step_path" -> kernel
+PATH_NAMES = {1: "k_step_walk", 2: "k_step_cycles", 3: "k_step_global", 4: "k_step_tile", 5: "k_step_band",
+              6: "W = I walk + k_spmm_rows", 7: "k_small_run"}
 
 
 def parse_args():
@@ -175,7 +167,7 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
             sim.step()
         sim.set_state(k=k_first)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-        kinds, offsets = [], []
+        kinds, offsets, paths = [], [], []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
@@ -187,6 +179,7 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
             ev[i][1].record()
             sim.step()
             ev[i][2].record()
+            paths.append((int(sim.query("step_path")), int(sim.query("step_paced"))))   # host-side facts, no synchronisation
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     grad_ms = [ev[i][0].elapsed_time(ev[i][1]) for i in range(steps)]
@@ -215,6 +208,9 @@ def run_workload(cfg_name, topology, steps, warmup, opts, copy_probe=0, trace=-1
     }
     dom = res["gossip_ms_avg"] if gossip else res["global_ms_avg"]
     res["dominant"] = "gossip" if gossip else "global"
+    # which kernels the gossip steps of the timed window ran as, as the library reports it
+    seen = sorted({p for p, kd in zip(paths, kinds) if kd == "gossip"})
+    res["gossip_kernels"] = [PATH_NAMES.get(p, str(p)) + (" (paced persistent launch)" if paced else "") for p, paced in seen]
     res["achieved_gbs"] = BYTES_PER_ELT * elts / (dom * 1e-3) / 1e9
     if glob:
         res["global_gbs"] = BYTES_PER_ELT * elts / (res["global_ms_avg"] * 1e-3) / 1e9
@@ -458,7 +454,7 @@ def main():
         return {
             "bound": "hbm",
             "workload": r["workload"],
-            "kernel": f"fused gossip step ({gossip_kernel_name(r['topology'], r['n'])})"
+            "kernel": f"fused gossip step ({'; '.join(r['gossip_kernels'])})"
                       if dom_gossip else "fused global-average step (k_step_global)",
             "achieved": r["achieved_gbs"],
             "peak": HBM_PEAK_GBS,
