@@ -185,3 +185,46 @@ def test_check_mixing_csr_accepts_doubly_stochastic_and_rejects_the_rest(lib):
     assert rejected(p3, col, val)
     nan = val.copy(); nan[1] = float("nan")
     assert rejected(ptr, col, nan)
+
+
+def test_the_header_is_plain_c_and_a_c_caller_links(tmp_path):
+    """include/gpga.h compiled as C99 (pedantic, warnings are errors) from a caller that walks through
+    the basic sequence of calls, linked against the built library (nothing runs: no GPU here)."""
+    import shutil
+    import subprocess
+    from paper_2105_09080_amd import build as gbuild
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "caller.c"
+    src.write_text(r'''
+#include <stddef.h>
+#include "gpga.h"
+int run(float* x, float* xn, float* m, float* g, int32_t n, int64_t d, void* stream, double* out) {
+    gpga_ctx* ctx = NULL;
+    float* live = NULL;
+    int64_t k;
+    if (gpga_create(&ctx, n, d, GPGA_TOPO_EXPO1, 6, 1e-4f, 0.9f) != GPGA_OK) return 1;
+    if (gpga_bind(ctx, x, xn, m, g, d, stream) != GPGA_OK) return 2;
+    if (gpga_problem_synthetic(ctx, 0u, 1e-3f) != GPGA_OK) return 3;
+    if (gpga_reset(ctx, NULL) != GPGA_OK) return 4;
+    for (k = 0; k < 12; ++k) {
+        if (gpga_local_grad(ctx, NULL, 0) != GPGA_OK) return 5;
+        if (gpga_step(ctx) != GPGA_OK) return 6;
+    }
+    if (gpga_current_x(ctx, &live) != GPGA_OK || live == NULL) return 7;
+    if (gpga_consensus_error(ctx, out) != GPGA_OK) return 8;
+    return gpga_destroy(ctx) == GPGA_OK ? 0 : 9;
+}
+int main(void) { return gpga_version() == NULL; }
+''')
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    obj = tmp_path / "caller.o"
+    res = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                          "-c", str(src), "-o", str(obj)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    if not os.path.exists(gbuild.LIB_PATH):
+        pytest.skip("library not built")
+    res = subprocess.run([gcc, str(obj), "-o", str(tmp_path / "caller"), gbuild.LIB_PATH,
+                          "-Wl,--unresolved-symbols=ignore-in-shared-libs"], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
