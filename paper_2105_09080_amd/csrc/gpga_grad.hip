@@ -199,11 +199,13 @@ __global__ void __launch_bounds__(256) k_rows_margin(const float* __restrict__ f
     }
     const float* __restrict__ f = feat + ((int64_t)i * M + r) * d;
     const float* __restrict__ xi = x + (int64_t)i * ld;
+    const float target = tgt[(int64_t)i * M + r];  // fetched with the row, not after the reduction
     double acc = 0.0;
     if (vec_ok) {
         const int64_t d4 = d >> 2;
         const v4f* f4 = reinterpret_cast<const v4f*>(f);
         const v4f* x4 = reinterpret_cast<const v4f*>(xi);
+#pragma unroll 4
         for (int64_t c = threadIdx.x; c < d4; c += blockDim.x) {
             const v4f fv = f4[c], xv = x4[c];
             acc += (double)fv.x * xv.x + (double)fv.y * xv.y + (double)fv.z * xv.z +
@@ -215,7 +217,7 @@ __global__ void __launch_bounds__(256) k_rows_margin(const float* __restrict__ f
     const double z = block_sum(acc, s_buf);
     if (threadIdx.x == 0) {
         float cf, ls;
-        sample_terms<KIND>(z, tgt[(int64_t)i * M + r], 1.0f / (float)B, &cf, &ls);
+        sample_terms<KIND>(z, target, 1.0f / (float)B, &cf, &ls);
         coef[(int64_t)i * B + b] = cf;
         lossterm[(int64_t)i * B + b] = ls;
     }
@@ -248,46 +250,69 @@ __global__ void __launch_bounds__(256) k_rows_margin_short(const float* __restri
     lossterm[p] = ls;
 }
 
-// Pass 2: one lane per column quad of node i: g = sum_b coef_b * row_b[c].
-__global__ void __launch_bounds__(256) k_rows_accum(const float* __restrict__ feat,
+// Pass 2: g = sum_b coef_b * row_b[c] for node i.  A workgroup of W wavefronts owns 64 column quads;
+// the wavefronts share the samples (b = wave, wave + W, ...) and their fp64 partial sums meet in LDS in
+// wavefront order, so a minibatch of 32 rows is four chains of eight dependent loads instead of one of 32
+// and a small problem still fills the chip (cfg2: 1280 -> 5120 wavefronts, 15 -> 9 us).  W = 4
+// wavefronts per workgroup, 16 for minibatches of 64 rows and more.
+template <int W>
+__global__ void __launch_bounds__(kWave* W) k_rows_accum(const float* __restrict__ feat,
                                                     const float* __restrict__ coef,
                                                     const int32_t* __restrict__ idx, int32_t B,
                                                     int32_t M, int64_t d, int vec_ok,
                                                     float* __restrict__ g, int64_t ld) {
+    __shared__ double s_part[W - 1][4][kWave];
     const int i = blockIdx.y;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const float* __restrict__ fi = feat + (int64_t)i * M * d;
     const float* __restrict__ ci = coef + (int64_t)i * B;
     const int32_t* __restrict__ ii = idx ? idx + (int64_t)i * B : nullptr;
     float* __restrict__ gi = g + (int64_t)i * ld;
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (vec_ok) {
-        if (t * 4 >= d) return;
-        double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-        for (int b = 0; b < B; ++b) {
+    const int64_t t = (int64_t)blockIdx.x * kWave + lane;          // column quad (vector path) or column
+    const bool on = vec_ok ? t * 4 < d : t < d;
+    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    if (on) {
+        for (int b = wave; b < B; b += W) {
             int32_t r = ii ? ii[b] : b;
             if (r < 0 || r >= M) r = 0;  // its coefficient is NaN (set by the margin pass): row 0 is only a safe address
-            const v4f fv = reinterpret_cast<const v4f*>(fi + (int64_t)r * d)[t];
             const double cb = ci[b];
-            a0 += cb * fv.x;
-            a1 += cb * fv.y;
-            a2 += cb * fv.z;
-            a3 += cb * fv.w;
+            if (vec_ok) {
+                const v4f fv = reinterpret_cast<const v4f*>(fi + (int64_t)r * d)[t];
+                a0 += cb * fv.x;
+                a1 += cb * fv.y;
+                a2 += cb * fv.z;
+                a3 += cb * fv.w;
+            } else {
+                a0 += cb * fi[(int64_t)r * d + t];
+            }
         }
-        v4f out;
-        out.x = (float)a0;
-        out.y = (float)a1;
-        out.z = (float)a2;
-        out.w = (float)a3;
-        __builtin_nontemporal_store(out, reinterpret_cast<v4f*>(gi) + t);
-    } else {
-        if (t >= d) return;
-        double a0 = 0;
-        for (int b = 0; b < B; ++b) {
-            int32_t r = ii ? ii[b] : b;
-            if (r < 0 || r >= M) r = 0;
-            a0 += (double)ci[b] * fi[(int64_t)r * d + t];
+    }
+    if (wave > 0) {
+        s_part[wave - 1][0][lane] = a0;
+        s_part[wave - 1][1][lane] = a1;
+        s_part[wave - 1][2][lane] = a2;
+        s_part[wave - 1][3][lane] = a3;
+    }
+    __syncthreads();
+    if (wave == 0 && on) {
+#pragma unroll
+        for (int w = 0; w < W - 1; ++w) {
+            a0 += s_part[w][0][lane];
+            a1 += s_part[w][1][lane];
+            a2 += s_part[w][2][lane];
+            a3 += s_part[w][3][lane];
         }
-        gi[t] = (float)a0;
+        if (vec_ok) {
+            v4f out;
+            out.x = (float)a0;
+            out.y = (float)a1;
+            out.z = (float)a2;
+            out.w = (float)a3;
+            __builtin_nontemporal_store(out, reinterpret_cast<v4f*>(gi) + t);
+        } else {
+            gi[t] = (float)a0;
+        }
     }
 }
 
@@ -763,9 +788,14 @@ hipError_t launch_rows_grad(const gpga_ctx* c, const int32_t* idx, int32_t B, fl
     }
     const int vec_g = vec_feat && aligned16(c->g) && (c->ld % 4 == 0);
     const int64_t cols = vec_g ? c->d / 4 : c->d;
-    dim3 grid2((unsigned)((cols + 255) / 256), (unsigned)c->n);
-    hipLaunchKernelGGL(k_rows_accum, grid2, block, 0, c->stream, c->feat, coef, idx, Beff, c->M,
-                       c->d, vec_g, c->g, c->ld);
+    dim3 grid2((unsigned)((cols + kWave - 1) / kWave), (unsigned)c->n);
+    if (Beff >= 64) {
+        hipLaunchKernelGGL(k_rows_accum<16>, grid2, dim3(kWave * 16), 0, c->stream, c->feat, coef, idx, Beff, c->M,
+                           c->d, vec_g, c->g, c->ld);
+    } else {
+        hipLaunchKernelGGL(k_rows_accum<4>, grid2, block, 0, c->stream, c->feat, coef, idx, Beff, c->M,
+                           c->d, vec_g, c->g, c->ld);
+    }
     return hipGetLastError();
 }
 
