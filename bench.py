@@ -36,12 +36,12 @@ BYTES_PER_ELT = 20             # read x, m, g; write m, x_new (fp32)
 MEASURED_TRAFFIC_BYTES = {
     # 12.000 B fetched + 8.000 B written per element in every case; where several kernels share the gossip steps
     # (one per one-peer offset class) the largest of their per-launch figures is given
-    "cfg3/ring": (32768441212, "profiles/step_cfg3_ring.md"),          # k_step_walk
-    "cfg3/expo1": (32768527749, "profiles/step_cfg3_expo1.md"),        # k_step_walk (offsets 1, 2), k_step_cycles (4 .. 32)
-    "cfg4/expo1": (140800598663, "profiles/step_cfg4_expo1.md"),       # k_step_walk (offset 1), k_step_cycles (2 .. 16)
-    "cfg5/ring": (20480463881, "profiles/step_cfg5_ring.md"),          # k_step_walk with the consensus trace riding along
-    "cfg3/grid": (32769093443, "profiles/step_sparse_cfg3_grid.md"),   # k_step_tile
-    "cfg5/grid": (20480760280, "profiles/step_sparse_cfg5_grid.md"),   # k_step_band with the consensus trace riding along
+    "cfg3/ring": (32768427004, "profiles/step_cfg3_ring.md"),          # k_step_walk
+    "cfg3/expo1": (32768515517, "profiles/step_cfg3_expo1.md"),        # k_step_walk (offsets 1, 2), k_step_cycles (4 .. 32)
+    "cfg4/expo1": (140800368980, "profiles/step_cfg4_expo1.md"),       # k_step_walk (offset 1), k_step_cycles (2 .. 16)
+    "cfg5/ring": (20480467145, "profiles/step_cfg5_ring.md"),          # k_step_walk with the consensus trace riding along
+    "cfg3/grid": (32768670746, "profiles/step_sparse_cfg3_grid.md"),   # k_step_tile
+    "cfg5/grid": (20480767643, "profiles/step_sparse_cfg5_grid.md"),   # k_step_band with the consensus trace riding along
 }
 
 
